@@ -1,0 +1,1 @@
+"""Independent CPU oracle (test infrastructure; never imported by the product path)."""

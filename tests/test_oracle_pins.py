@@ -1,0 +1,451 @@
+"""Pins for the CPU oracle: every check compares it with something other than itself —
+a closed form, a textbook special case, brute force (sequential decoding), or an
+independently assembled forward pass built from PyTorch CPU ops in the padded,
+densely masked formulation (paper section 4.3, "Processing heterogeneous requests").
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import verify_oracle as vo
+from tests.helpers import oracle_model, corrupt_chain
+
+SHAPE = synth.TINY
+SEED = 11
+
+
+@pytest.fixture(scope="module")
+def model():
+    return oracle_model(SHAPE, SEED)
+
+
+@pytest.fixture(scope="module")
+def base_cache(model):
+    toks = synth.rng.uniform_i32(5, 1, 40, 0, SHAPE.vocab)
+    return vo.prefill(model, toks, 96), toks
+
+
+# ---------------------------------------------------------------------------
+# primitives against closed forms
+# ---------------------------------------------------------------------------
+
+
+def test_rmsnorm_closed_form():
+    x = np.array([[3.0, 4.0]])
+    got = vo.rmsnorm(x, 1.0, 0.0)
+    assert np.allclose(got, x / math.sqrt(12.5), atol=1e-15)
+    # constant vector -> sign * gain (eps -> 0)
+    got = vo.rmsnorm(np.full((1, 8), -2.5), np.arange(1.0, 9.0), 0.0)
+    assert np.allclose(got, -np.arange(1.0, 9.0), atol=1e-15)
+    # eps sits inside the root: x=0 stays 0, and a tiny vector is damped by sqrt(eps)
+    tiny = vo.rmsnorm(np.full((1, 4), 1e-6), 1.0, 1e-5)
+    assert np.allclose(tiny, 1e-6 / math.sqrt(1e-12 + 1e-5), rtol=1e-12)
+
+
+def test_silu_values():
+    assert np.allclose(vo.silu(np.array([0.0, 1.0, -1.0, 20.0])),
+                       [0.0, 0.7310585786300049, -0.2689414213699951, 20.0 / (1 + math.exp(-20.0))], atol=1e-15)
+
+
+def test_rope_closed_form_and_invariants():
+    # hd = 2: a single pair rotated by angle pos * base**0 = pos
+    x = np.array([[[1.0, 0.0]], [[0.0, 1.0]], [[2.0, -1.0]]])
+    pos = np.array([0.5, 0.5, 3.0])
+    got = vo.rope(x, pos, 10000.0)
+    for r in range(3):
+        c, s = math.cos(pos[r]), math.sin(pos[r])
+        a, b = x[r, 0]
+        assert np.allclose(got[r, 0], [a * c - b * s, b * c + a * s], atol=1e-15)
+    # hd = 4, base 10000: second pair (elements 1 and 3) turns at 10000**(-2/4) = 0.01 rad per position
+    y = np.zeros((1, 1, 4)); y[0, 0, 1] = 1.0
+    got = vo.rope(y, np.array([7.0]), 10000.0)[0, 0]
+    assert np.allclose(got, [0.0, math.cos(0.07), 0.0, math.sin(0.07)], atol=1e-15)
+    # position 0 is the identity; the norm is preserved; q.k depends only on the position difference
+    rs = np.random.default_rng(0)
+    q, k = rs.standard_normal((1, 2, 64)), rs.standard_normal((1, 2, 64))
+    assert np.array_equal(vo.rope(q, np.array([0]), 5e5), q)
+    assert np.allclose(np.linalg.norm(vo.rope(q, np.array([123]), 5e5)), np.linalg.norm(q), rtol=1e-13)
+    d1 = np.sum(vo.rope(q, np.array([17]), 5e5) * vo.rope(k, np.array([5]), 5e5), axis=-1)
+    d2 = np.sum(vo.rope(q, np.array([1012]), 5e5) * vo.rope(k, np.array([1000]), 5e5), axis=-1)
+    assert np.allclose(d1, d2, atol=1e-10)
+    # and it is NOT symmetric in the sign of the difference
+    d3 = np.sum(vo.rope(q, np.array([5]), 5e5) * vo.rope(k, np.array([17]), 5e5), axis=-1)
+    assert not np.allclose(d1, d3, atol=1e-6)
+
+
+def test_attention_special_cases():
+    rs = np.random.default_rng(1)
+    # one visible key -> returns its value, for every head
+    q = rs.standard_normal((3, 4, 8)); K = rs.standard_normal((5, 2, 8)); V = rs.standard_normal((5, 2, 8))
+    mask = np.zeros((3, 5), dtype=bool); mask[:, 2] = True
+    out = vo.attention(q, K, V, mask)
+    for j in range(4):
+        assert np.allclose(out[:, j], V[2, j // 2], atol=1e-15)
+    # identical keys -> plain mean of the visible values (checks the mask and the normalisation)
+    K2 = np.repeat(K[:1], 5, axis=0)
+    mask = np.tril(np.ones((3, 5), dtype=bool), k=2)
+    out = vo.attention(q, K2, V, mask)
+    for i in range(3):
+        vis = V[:i + 3]
+        for j in range(4):
+            assert np.allclose(out[i, j], vis[:, j // 2].mean(axis=0), atol=1e-14)
+    # grouped-query mapping: head j reads KV head floor(j*Hkv/Hq); values carry their head index
+    Vtag = np.zeros((5, 2, 8)); Vtag[:, 1] = 1.0
+    out = vo.attention(q, K, Vtag, np.ones((3, 5), dtype=bool))
+    assert np.allclose(out[:, :2], 0.0) and np.allclose(out[:, 2:], 1.0)
+    # two keys, known scores: weights are softmax of q.k/sqrt(hd)
+    q1 = np.zeros((1, 1, 4)); q1[0, 0, 0] = 2.0
+    K1 = np.zeros((2, 1, 4)); K1[0, 0, 0] = 1.0; K1[1, 0, 0] = -1.0
+    V1 = np.array([[[1.0, 0, 0, 0]], [[0.0, 1.0, 0, 0]]])
+    out = vo.attention(q1, K1, V1, np.ones((1, 2), dtype=bool))[0, 0]
+    w0 = 1.0 / (1.0 + math.exp(-2.0))          # scores +1 and -1 after the 1/sqrt(4) scale
+    assert np.allclose(out[:2], [w0, 1 - w0], atol=1e-15)
+
+
+def test_gqa_with_all_heads_equals_mha():
+    """Hkv == Hq: every query head has its own KV head (textbook multi-head attention)."""
+    rs = np.random.default_rng(2)
+    q = rs.standard_normal((4, 3, 8)); K = rs.standard_normal((6, 3, 8)); V = rs.standard_normal((6, 3, 8))
+    mask = np.ones((4, 6), dtype=bool)
+    out = vo.attention(q, K, V, mask)
+    tq, tK, tV = (torch.from_numpy(a).permute(1, 0, 2) for a in (q, K, V))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tK, tV).permute(1, 0, 2).numpy()
+    assert np.allclose(out, ref, atol=1e-12)
+
+
+def test_tree_helpers():
+    par = np.array([-1, 0, 0, 1, -1, 3])
+    assert list(vo.depths(par)) == [0, 1, 1, 2, 0, 3]
+    m = vo.ancestor_mask(par)
+    want = {0: {0}, 1: {0, 1}, 2: {0, 2}, 3: {0, 1, 3}, 4: {4}, 5: {0, 1, 3, 5}}
+    for i in range(6):
+        assert set(np.nonzero(m[i])[0]) == want[i]
+    assert np.array_equal(vo.ancestor_mask(vo.chain_parents(5)), np.tril(np.ones((5, 5), dtype=bool)))
+
+
+# ---------------------------------------------------------------------------
+# acceptance rule, hand-worked cases and a closed-form statistic
+# ---------------------------------------------------------------------------
+
+
+def test_accept_chain_hand_cases():
+    am = np.array([11, 12, 13, 14])                   # target's choice AFTER each draft position
+    assert vo.accept_chain(np.array([10, 11, 12, 13]), 10, am) == (4, 14, [0, 1, 2, 3])
+    assert vo.accept_chain(np.array([99, 11, 12, 13]), 10, am) == (0, 10, [])
+    assert vo.accept_chain(np.array([10, 11, 77, 13]), 10, am) == (2, 12, [0, 1])
+    assert vo.accept_chain(np.array([], dtype=np.int64), 10, np.array([], dtype=np.int64)) == (0, 10, [])
+
+
+def test_accept_tree_hand_cases():
+    #        prefix --- 0(t=5) --- 2(t=7) --- 4(t=9)
+    #            \            \--- 3(t=8)
+    #             \---- 1(t=6) --- 5(t=7)
+    par = np.array([-1, -1, 0, 0, 2, 1])
+    tok = np.array([5, 6, 7, 8, 9, 7])
+    am = np.array([8, 7, 9, 1, 2, 3])                 # after node0 target says 8, after node3 says 1 ...
+    assert vo.accept_tree(tok, par, 5, am) == (2, 1, [0, 3])
+    assert vo.accept_tree(tok, par, 6, am) == (2, 3, [1, 5])
+    assert vo.accept_tree(tok, par, 4, am) == (0, 4, [])
+    am2 = np.array([7, 7, 9, 1, 2, 3])
+    assert vo.accept_tree(tok, par, 5, am2) == (3, 2, [0, 2, 4])
+    # a chain written as a tree gives the chain result
+    c = np.array([10, 11, 77, 13]); amc = np.array([11, 12, 13, 14])
+    assert vo.accept_tree(c, vo.chain_parents(4), 10, amc) == vo.accept_chain(c, 10, amc)
+
+
+def test_accept_tree_equals_longest_matching_path_bruteforce():
+    """With distinct sibling tokens the greedy descent is the longest root-to-leaf path whose
+    tokens all equal the target's prediction given the path so far (brute force over all paths)."""
+    rs = np.random.default_rng(3)
+    for trial in range(200):
+        n = 12
+        par = np.array([-1] + [int(rs.integers(-1, i)) for i in range(1, n)])
+        tok = np.empty(n, dtype=np.int64)
+        for p in set(par.tolist()):
+            kids = np.nonzero(par == p)[0]
+            tok[kids] = rs.choice(6, size=len(kids), replace=False)
+        am = rs.integers(0, 6, size=n)
+        nt = int(rs.integers(0, 6))
+        best = []
+        for leaf in range(n):
+            path, j = [], leaf
+            while j >= 0:
+                path.append(j); j = int(par[j])
+            path = path[::-1]
+            ok = all(tok[c] == (nt if i == 0 else am[path[i - 1]]) for i, c in enumerate(path))
+            if ok and len(path) > len(best):
+                best = path
+        a, bonus, path = vo.accept_tree(tok, par, nt, am)
+        assert path == best and a == len(best)
+        assert bonus == (nt if not best else am[best[-1]])
+
+
+def test_expected_accept_length_closed_form():
+    """Corrupting each position independently with probability p by a uniform id gives
+    E[accept_len] = sum_{j=1..k} q^j with q = 1 - p(1 - 1/V)."""
+    k, p, V, trials = 8, 0.3, 50, 40000
+    g = synth.rng.uniform_i32(9, 1, (k + 1) * trials, 0, V).reshape(trials, k + 1)
+    draw = synth.rng.uniform_f64(9, 2, k * trials).reshape(trials, k)
+    rnd = synth.rng.uniform_i32(9, 3, k * trials, 0, V).reshape(trials, k)
+    tot = 0
+    for t in range(trials):
+        d = np.where(draw[t] < p, rnd[t], g[t, :k])
+        tot += vo.accept_chain(d, g[t, 0], g[t, 1:])[0]
+    q = 1 - p * (1 - 1 / V)
+    want = sum(q ** j for j in range(1, k + 1))
+    assert abs(tot / trials - want) < 4 * 2.0 / math.sqrt(trials)      # 4 sigma, sd(accept_len) < 2
+
+
+# ---------------------------------------------------------------------------
+# whole forward against an independently assembled one (padded + dense mask, torch ops)
+# ---------------------------------------------------------------------------
+
+
+def torch_padded_forward(shape, weights, prefix_tok_lists, block_tok_lists, parent_lists):
+    """Logits of the block tokens, computed the way the paper states it: every sequence
+    (prefix + block) padded to the longest one in the batch, one dense additive mask.
+    Written only with torch ops; RoPE as a complex multiplication."""
+    t64 = torch.float64
+    W = {k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in weights.items()}
+    B = len(prefix_tok_lists)
+    Ps = [len(p) for p in prefix_tok_lists]
+    ns = [len(b) for b in block_tok_lists]
+    T = max(P + n for P, n in zip(Ps, ns))
+    ids = torch.zeros(B, T, dtype=torch.long)
+    pos = torch.zeros(B, T, dtype=t64)
+    allow = torch.zeros(B, T, T, dtype=torch.bool)
+    for b in range(B):
+        P, n = Ps[b], ns[b]
+        ids[b, :P] = torch.as_tensor(np.asarray(prefix_tok_lists[b]), dtype=torch.long)
+        ids[b, P:P + n] = torch.as_tensor(np.asarray(block_tok_lists[b]), dtype=torch.long)
+        pos[b, :P] = torch.arange(P, dtype=t64)
+        allow[b, :P, :P] = torch.tril(torch.ones(P, P, dtype=torch.bool))
+        par = parent_lists[b]
+        for i in range(n):
+            depth, j = 0, i
+            allow[b, P + i, :P] = True
+            while j >= 0:
+                allow[b, P + i, P + j] = True
+                j = int(par[j]); depth += 1
+            pos[b, P + i] = P + depth - 1
+        for t in range(P + n, T):
+            allow[b, t, t] = True                       # padded rows: keep softmax finite; never read
+    bias = torch.where(allow, 0.0, float("-inf")).to(t64)[:, None]           # [B,1,T,T]
+    Hq, Hkv, hd = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    freqs = shape.rope_base ** (-torch.arange(0, hd, 2, dtype=t64) / hd)
+    rot = torch.polar(torch.ones(B, T, hd // 2, dtype=t64), pos[..., None] * freqs)      # e^{i pos theta}
+
+    def rotate(x):                                       # x [B,T,H,hd], pairs (i, i+hd/2)
+        z = torch.complex(x[..., :hd // 2], x[..., hd // 2:]) * rot[:, :, None, :]
+        return torch.cat([z.real, z.imag], dim=-1)
+
+    def norm(x):
+        return x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + shape.rms_eps)
+
+    h = W["embed"][ids]
+    for l in range(shape.n_layers):
+        x = norm(h)
+        q = rotate(torch.nn.functional.linear(x, W[f"wq{l}"]).view(B, T, Hq, hd))
+        k = rotate(torch.nn.functional.linear(x, W[f"wk{l}"]).view(B, T, Hkv, hd))
+        v = torch.nn.functional.linear(x, W[f"wv{l}"]).view(B, T, Hkv, hd)
+        k = k.repeat_interleave(Hq // Hkv, dim=2)
+        v = v.repeat_interleave(Hq // Hkv, dim=2)
+        s = torch.einsum("bthd,bshd->bhts", q, k) / math.sqrt(hd) + bias
+        o = torch.einsum("bhts,bshd->bthd", torch.softmax(s, dim=-1), v).reshape(B, T, Hq * hd)
+        h = h + torch.nn.functional.linear(o, W[f"wo{l}"])
+        x = norm(h)
+        h = h + torch.nn.functional.linear(
+            torch.nn.functional.silu(torch.nn.functional.linear(x, W[f"wg{l}"])) * torch.nn.functional.linear(x, W[f"wu{l}"]),
+            W[f"wd{l}"])
+    logits = torch.nn.functional.linear(norm(h), W["lm_head"])
+    return [logits[b, Ps[b]:Ps[b] + ns[b]].numpy() for b in range(B)]
+
+
+def _weights_dict(shape, seed):
+    src = synth.WeightSource(shape, seed)
+    W = {"embed": src.tensor_f32("embed"), "lm_head": src.tensor_f32("lm_head")}
+    for l in range(shape.n_layers):
+        for nme in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+            W[f"{nme}{l}"] = src.tensor_f32(nme, l)
+    return W
+
+
+@pytest.mark.parametrize("shape", [synth.TINY, synth.MINI_BF16.with_layers(2)], ids=["mha-hd64", "gqa-hd128"])
+def test_ragged_oracle_equals_padded_dense_torch_forward(shape):
+    """Heterogeneous lengths in one batch, chain and tree blocks: the ragged per-request oracle
+    equals the padded, densely masked batch forward (independent code: torch ops, complex RoPE)."""
+    seed = 21
+    m = oracle_model(shape, seed)
+    W = _weights_dict(shape, seed)
+    lens = [5, 23, 12]
+    prefixes = [synth.rng.uniform_i32(seed, 100 + b, P, 0, shape.vocab) for b, P in enumerate(lens)]
+    caches = [vo.prefill(m, p, 64) for p in prefixes]
+    blocks = [synth.rng.uniform_i32(seed, 200 + b, n, 0, shape.vocab) for b, n in enumerate([4, 7, 6])]
+    pars = [vo.chain_parents(4), np.array([-1, 0, 0, 1, 1, 2, 5]), np.array([-1, -1, 0, 1, 3, 3])]
+    got, _, _ = vo.forward_blocks(m, caches, blocks, pars)
+    ref = torch_padded_forward(shape, W, prefixes, blocks, pars)
+    for b in range(3):
+        assert np.max(np.abs(got[b] - ref[b])) < 1e-9
+    # the prefill's own next_tok agrees with the padded forward run on the prefix alone
+    ref_last = torch_padded_forward(shape, W, [p[:-1] for p in prefixes], [p[-1:] for p in prefixes],
+                                    [np.array([-1])] * 3)
+    for b in range(3):
+        assert caches[b].next_tok == int(np.argmax(ref_last[b][0]))
+
+
+# ---------------------------------------------------------------------------
+# brute force: one block verify == k sequential single-token decodes
+# ---------------------------------------------------------------------------
+
+
+def test_block_verify_equals_sequential_decodes(model, base_cache):
+    cache, _ = base_cache
+    k = 6
+    drafts = synth.rng.uniform_i32(7, 1, k, 0, SHAPE.vocab)
+    res = vo.verify(model, [cache.copy()], [drafts])[0]
+    seq = cache.copy()
+    for i in range(k):
+        lg = vo.extend(model, [seq], [drafts[i:i + 1]])[0]
+        assert np.max(np.abs(lg[0] - res.logits[i])) < 1e-10
+        assert int(np.argmax(lg[0])) == int(res.argmax[i])
+    # k = 1 verify is an ordinary decode step
+    one = vo.verify(model, [cache.copy()], [drafts[:1]])[0]
+    assert np.max(np.abs(one.logits[0] - res.logits[0])) < 1e-10
+
+
+def test_perfect_drafts_fully_accepted_and_first_corruption_rejects_all(model, base_cache):
+    cache, _ = base_cache
+    k = 5
+    g = vo.greedy_continuation(model, [cache], k)[0]
+    r = vo.verify(model, [cache.copy()], [g[:k]])[0]
+    assert r.accept_len == k and r.bonus_token == g[k] and r.path == list(range(k))
+    for j in range(k):                                   # single corruption at j -> accept j, bonus g_j
+        d = g[:k].copy()
+        d[j] = (d[j] + 1) % SHAPE.vocab
+        r = vo.verify(model, [cache.copy()], [d])[0]
+        assert r.accept_len == j and r.bonus_token == g[j]
+    assert vo.verify(model, [cache.copy()], [np.concatenate([[(g[0] + 5) % SHAPE.vocab], g[1:k]])])[0].accept_len == 0
+
+
+def test_multi_round_losslessness(model, base_cache):
+    """Verify+commit rounds with arbitrary drafts emit exactly plain greedy decoding
+    (paper section 4.1: the output equals what the server model alone would generate)."""
+    cache, _ = base_cache
+    total = 14
+    g = vo.greedy_continuation(model, [cache], total + 8)[0]
+    for mode in ("random", "perfect", "half"):
+        c = cache.copy()
+        emitted, rnd = [], 0
+        while len(emitted) < total:
+            P0 = c.length - base_cache[0].length
+            if mode == "random":
+                # the edge resends the server's extra token as its first candidate, then guesses blindly
+                d = synth.rng.uniform_i32(31, rnd, 4, 0, SHAPE.vocab).astype(np.int64)
+                d[0] = c.next_tok
+            elif mode == "perfect":
+                d = g[P0:P0 + 4].copy()
+            else:
+                d = g[P0:P0 + 4].copy(); d[2] = (d[2] + 3) % SHAPE.vocab
+            if rnd % 3 == 2:                              # a rollback in between must change nothing
+                vo.verify(model, [c], [d]); vo.rollback(c)
+            r = vo.verify(model, [c], [d])[0]
+            vo.commit(model, c)
+            emitted += [int(t) for t in d[:r.accept_len]]
+            assert c.next_tok == r.bonus_token
+            rnd += 1
+        n = len(emitted)
+        assert emitted == [int(t) for t in g[:n]]
+        assert c.next_tok == g[n]
+
+
+def test_commit_equals_fresh_prefill(model, base_cache):
+    cache, toks = base_cache
+    g = vo.greedy_continuation(model, [cache], 4)[0]
+    d = g[:4].copy(); d[3] = (d[3] + 1) % SHAPE.vocab
+    c = cache.copy()
+    r = vo.verify(model, [c], [d])[0]
+    assert r.accept_len == 3
+    vo.commit(model, c)
+    fresh = vo.prefill(model, np.concatenate([toks, d[:3]]), 96)
+    assert c.length == fresh.length and c.next_tok == fresh.next_tok
+    for l in range(SHAPE.n_layers):
+        assert np.max(np.abs(c.K[l][:c.length] - fresh.K[l][:c.length])) < 1e-11
+        assert np.max(np.abs(c.V[l][:c.length] - fresh.V[l][:c.length])) < 1e-11
+    # rollback then the same verify gives the same answer
+    c2 = cache.copy()
+    vo.verify(model, [c2], [d]); vo.rollback(c2)
+    r2 = vo.verify(model, [c2], [d])[0]
+    assert r2.accept_len == r.accept_len and r2.bonus_token == r.bonus_token
+    assert np.array_equal(r2.logits, r.logits)
+
+
+def test_tree_chain_equivalence_and_tree_commit(model, base_cache):
+    cache, toks = base_cache
+    g = vo.greedy_continuation(model, [cache], 4)[0]
+    # chain written as a tree: identical logits and result
+    rc = vo.verify(model, [cache.copy()], [g[:4]])[0]
+    rt = vo.verify(model, [cache.copy()], [g[:4]], [vo.chain_parents(4)])[0]
+    assert np.array_equal(rc.logits, rt.logits) and (rc.accept_len, rc.bonus_token) == (rt.accept_len, rt.bonus_token)
+    # a tree that contains the greedy path among wrong siblings: path found, commit == prefill of accepted tokens
+    V = SHAPE.vocab
+    par = np.array([-1, -1, 1, 1, 0, 3, 3, 5])
+    tok = np.array([(g[0] + 1) % V, g[0], (g[1] + 1) % V, g[1], g[1], g[2], (g[2] + 2) % V, (g[3] + 1) % V])
+    c = cache.copy()
+    r = vo.verify(model, [c], [tok], [par])[0]
+    assert r.path == [1, 3, 5] and r.accept_len == 3 and r.bonus_token == g[3]
+    vo.commit(model, c)
+    fresh = vo.prefill(model, np.concatenate([toks, g[:3]]), 96)
+    assert c.next_tok == fresh.next_tok
+    for l in range(SHAPE.n_layers):
+        assert np.max(np.abs(c.K[l][:c.length] - fresh.K[l][:c.length])) < 1e-11
+    # relabelling siblings (same topology, children listed in another order) leaves the accepted tokens unchanged
+    perm = np.array([1, 0, 3, 2, 4, 6, 5, 7])           # new index -> old index
+    inv = np.argsort(perm)
+    par2 = np.array([-1 if par[o] < 0 else inv[par[o]] for o in perm])
+    assert all(par2[i] < i for i in range(8))
+    r2 = vo.verify(model, [cache.copy()], [tok[perm]], [par2])[0]
+    assert [int(tok[perm][i]) for i in r2.path] == [int(tok[i]) for i in r.path] and r2.bonus_token == r.bonus_token
+
+
+def test_batch_invariance(model):
+    """Per-request results do not depend on batch composition or order (section 4.3:
+    no cross-sequence interference)."""
+    lens = [9, 30, 17]
+    caches = [vo.prefill(model, synth.rng.uniform_i32(41, b, P, 0, SHAPE.vocab), 64) for b, P in enumerate(lens)]
+    drafts = [synth.rng.uniform_i32(42, b, n, 0, SHAPE.vocab) for b, n in enumerate([3, 8, 5])]
+    solo = [vo.verify(model, [caches[b].copy()], [drafts[b]])[0] for b in range(3)]
+    both = vo.verify(model, [c.copy() for c in caches], drafts)
+    rev = vo.verify(model, [c.copy() for c in caches[::-1]], drafts[::-1])[::-1]
+    for b in range(3):
+        for other in (both[b], rev[b]):
+            assert np.max(np.abs(other.logits - solo[b].logits)) < 1e-11
+            assert (other.accept_len, other.bonus_token) == (solo[b].accept_len, solo[b].bonus_token)
+
+
+def test_float32_oracle_tracks_float64(model, base_cache):
+    """The float32 mode used for the large shapes differs from float64 by reassociation error only."""
+    m32 = oracle_model(SHAPE, SEED, dtype=np.float32)
+    _, toks = base_cache
+    c32 = vo.prefill(m32, toks, 96)
+    c64 = base_cache[0]
+    d = synth.rng.uniform_i32(7, 1, 6, 0, SHAPE.vocab)
+    r32 = vo.verify(m32, [c32], [d])[0]
+    r64 = vo.verify(model, [c64.copy()], [d])[0]
+    assert r32.logits.dtype == np.float32
+    assert np.max(np.abs(r32.logits - r64.logits)) < 2e-5
+
+
+def test_workload_chain_recipe(model):
+    """Config-1 recipe end to end on the oracle: prefill 64 ids, k=4 greedy continuation with p=0.3 corruption."""
+    wl = synth.WORKLOADS["tiny-chain"]
+    m = oracle_model(wl.shape, wl.seed)
+    req = synth.make_requests(wl)[0]
+    c = vo.prefill(m, req.prefix_tokens, 80)
+    g = vo.greedy_continuation(m, [c], 4)[0]
+    d = corrupt_chain(g, req, 4)
+    r = vo.verify(m, [c], [d])[0]
+    first_bad = next((j for j in range(4) if d[j] != g[j]), 4)
+    assert r.accept_len == first_bad and r.bonus_token == g[first_bad]
