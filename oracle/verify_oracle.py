@@ -33,6 +33,10 @@ reassociation error is at stake).
 Readings of points the paper leaves open (all conventions, parity unpinned
 against any external implementation): RoPE pairs element i with i+hd/2 and uses
 angle pos * base**(-2i/hd); RMSNorm epsilon sits inside the square root;
+a model whose KV cache is bfloat16 (`kv_bf16`) rounds every key (after the
+rotation) and value to nearest-even bfloat16 where it enters the cache, and the
+block's own attention reads those stored values - the cache format is part of
+the model, everything else stays in `model.dtype`;
 arg-max ties go to the lowest token id; the first candidate of a block is
 checked against `next_tok`, the target's own prediction after the committed
 prefix, which the cache carries from the previous step; a tree node sits at
@@ -69,6 +73,7 @@ class Model:
     tensor: Callable[[str, int], np.ndarray]
     dtype: type = np.float64
     cache_weights: bool = True
+    kv_bf16: bool = False            # the KV cache stores bfloat16 (round-to-nearest-even on write)
     _memo: dict = field(default_factory=dict, repr=False)
 
     def w(self, name: str, layer: int = 0) -> np.ndarray:
@@ -166,6 +171,24 @@ def attention(q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: np.ndarray) -> 
     return out
 
 
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Round to the nearest bfloat16 (ties to even), returned in x's dtype.
+
+    bfloat16 keeps the sign, the 8-bit exponent and the top 7 fraction bits of a
+    float32.  float64 input is rounded in ONE step to those 7 fraction bits (valid
+    for magnitudes inside bfloat16's normal range, or exactly zero)."""
+    if x.dtype == np.float64:
+        a = np.abs(x)
+        assert np.all((a == 0) | ((a > 1.2e-38) & (a < 3.3e38))), "outside bfloat16 normal range"
+        u = np.ascontiguousarray(x).view(np.uint64)
+        drop = np.uint64(45)                               # 52 fraction bits -> 7
+        r = (u + np.uint64((1 << 44) - 1) + ((u >> drop) & np.uint64(1))) >> drop << drop
+        return r.view(np.float64).reshape(x.shape)
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16) << np.uint32(16)
+    return r.view(np.float32).reshape(x.shape).astype(x.dtype)
+
+
 def silu(x: np.ndarray) -> np.ndarray:
     return x / (1.0 + np.exp(-x))
 
@@ -238,6 +261,8 @@ def forward_blocks(model: Model, caches: Sequence[Cache], tokens: Sequence[np.nd
         v = (x @ m.w("wv", l).T).reshape(M, m.n_kv_heads, m.head_dim)
         q = rope(q, pos, m.rope_base)
         k = rope(k, pos, m.rope_base)
+        if m.kv_bf16:
+            k, v = round_bf16(k), round_bf16(v)
         o = np.empty_like(q)
         for r in range(R):
             a, b = offs[r], offs[r + 1]

@@ -10,7 +10,8 @@ def oracle_model(shape: synth.ModelShape, seed: int, dtype=np.float64, cache_wei
     src = synth.WeightSource(shape, seed)
     return vo.Model(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                     shape.d_ffn, shape.vocab, shape.rope_base, shape.rms_eps,
-                    tensor=src.tensor_f32, dtype=dtype, cache_weights=cache_weights)
+                    tensor=src.tensor_f32, dtype=dtype, cache_weights=cache_weights,
+                    kv_bf16=(shape.dtype == "bf16"))
 
 
 def corrupt_chain(greedy: np.ndarray, req: synth.workload.Request, n: int) -> np.ndarray:

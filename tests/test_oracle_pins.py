@@ -116,6 +116,21 @@ def test_gqa_with_all_heads_equals_mha():
     assert np.allclose(out, ref, atol=1e-12)
 
 
+def test_round_bf16_matches_library_cast_and_hand_cases():
+    rs = np.random.default_rng(5)
+    x = (rs.standard_normal(100000) * np.exp(rs.uniform(-20, 20, 100000))).astype(np.float32)
+    ties = np.array([1.00390625, 1.01171875, -1.00390625, 3.0, 0.0, 255.5, 1.99609375], dtype=np.float32)
+    x = np.concatenate([x, ties])
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(vo.round_bf16(x), ref)
+    assert np.array_equal(vo.round_bf16(x.astype(np.float64)), ref.astype(np.float64))
+    # float64 values just above / below a tie are rounded in one step (no detour through float32)
+    assert vo.round_bf16(np.array([1.00390625 * (1 + 1e-12)]))[0] == 1.0078125
+    assert vo.round_bf16(np.array([1.00390625 * (1 - 1e-12)]))[0] == 1.0
+    assert vo.round_bf16(np.array([1.00390625]))[0] == 1.0            # exact tie -> even
+    assert vo.round_bf16(np.array([1.01171875]))[0] == 1.015625       # exact tie -> even (upwards)
+
+
 def test_tree_helpers():
     par = np.array([-1, 0, 0, 1, -1, 3])
     assert list(vo.depths(par)) == [0, 1, 1, 2, 0, 3]
@@ -204,7 +219,7 @@ def test_expected_accept_length_closed_form():
 # ---------------------------------------------------------------------------
 
 
-def torch_padded_forward(shape, weights, prefix_tok_lists, block_tok_lists, parent_lists):
+def torch_padded_forward(shape, weights, prefix_tok_lists, block_tok_lists, parent_lists, kv_bf16=False):
     """Logits of the block tokens, computed the way the paper states it: every sequence
     (prefix + block) padded to the longest one in the batch, one dense additive mask.
     Written only with torch ops; RoPE as a complex multiplication."""
@@ -251,6 +266,12 @@ def torch_padded_forward(shape, weights, prefix_tok_lists, block_tok_lists, pare
         q = rotate(torch.nn.functional.linear(x, W[f"wq{l}"]).view(B, T, Hq, hd))
         k = rotate(torch.nn.functional.linear(x, W[f"wk{l}"]).view(B, T, Hkv, hd))
         v = torch.nn.functional.linear(x, W[f"wv{l}"]).view(B, T, Hkv, hd)
+        if kv_bf16:                                      # the cache stores bfloat16
+            # 8 significant bits, ties to even, in one step (a cast through float32 would round twice)
+            def r8(t):
+                mant, expo = torch.frexp(t)
+                return torch.ldexp(torch.round(mant * 256.0), expo - 8)
+            k, v = r8(k), r8(v)
         k = k.repeat_interleave(Hq // Hkv, dim=2)
         v = v.repeat_interleave(Hq // Hkv, dim=2)
         s = torch.einsum("bthd,bshd->bhts", q, k) / math.sqrt(hd) + bias
@@ -278,7 +299,9 @@ def test_ragged_oracle_equals_padded_dense_torch_forward(shape):
     """Heterogeneous lengths in one batch, chain and tree blocks: the ragged per-request oracle
     equals the padded, densely masked batch forward (independent code: torch ops, complex RoPE)."""
     seed = 21
+    kvb = shape.dtype == "bf16"
     m = oracle_model(shape, seed)
+    assert m.kv_bf16 == kvb
     W = _weights_dict(shape, seed)
     lens = [5, 23, 12]
     prefixes = [synth.rng.uniform_i32(seed, 100 + b, P, 0, shape.vocab) for b, P in enumerate(lens)]
@@ -286,12 +309,12 @@ def test_ragged_oracle_equals_padded_dense_torch_forward(shape):
     blocks = [synth.rng.uniform_i32(seed, 200 + b, n, 0, shape.vocab) for b, n in enumerate([4, 7, 6])]
     pars = [vo.chain_parents(4), np.array([-1, 0, 0, 1, 1, 2, 5]), np.array([-1, -1, 0, 1, 3, 3])]
     got, _, _ = vo.forward_blocks(m, caches, blocks, pars)
-    ref = torch_padded_forward(shape, W, prefixes, blocks, pars)
+    ref = torch_padded_forward(shape, W, prefixes, blocks, pars, kvb)
     for b in range(3):
         assert np.max(np.abs(got[b] - ref[b])) < 1e-9
     # the prefill's own next_tok agrees with the padded forward run on the prefix alone
     ref_last = torch_padded_forward(shape, W, [p[:-1] for p in prefixes], [p[-1:] for p in prefixes],
-                                    [np.array([-1])] * 3)
+                                    [np.array([-1])] * 3, kvb)
     for b in range(3):
         assert caches[b].next_tok == int(np.argmax(ref_last[b][0]))
 
