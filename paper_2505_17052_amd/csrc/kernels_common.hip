@@ -1,0 +1,334 @@
+// Kernels shared by both precisions: call plan, acceptance, KV commit, cache import/export.
+#include "sev_internal.h"
+#include "kv_layout.h"
+
+// ---------------------------------------------------------------------------
+// fills
+// ---------------------------------------------------------------------------
+__global__ void fill_f32_kernel(float *p, float v, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+__global__ void fill_i32_kernel(int32_t *p, int32_t v, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+void launch_fill_f32(float *p, float v, int64_t n, hipStream_t st) {
+    if (n > 0) hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+}
+void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st) {
+    if (n > 0) hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+}
+
+// ---------------------------------------------------------------------------
+// call plan: everything the forward pass needs to know about the batch,
+// derived on the device from the lengths passed by value.
+//
+// Per request: row range, prefix length, slot.  Per draft node (row): request,
+// node index, rotary position P + depth, ancestor-or-self bit mask, token.
+// Per row and rotary frequency: (cos, sin) of pos * base^(-2i/hd), evaluated in
+// double so that positions in the thousands keep full float accuracy.
+// For the matrix-core attention: the list of (request, row group, KV chunk)
+// work items and the per (request, row group) merge groups.
+// ---------------------------------------------------------------------------
+struct PlanDev {
+    DevPlan p;
+    int32_t *seq_len, *pend_n, *pend_P;
+    uint32_t *err;
+    int vocab, hd, G;          // G = query heads per KV head
+    double rope_base;
+    int chunk_pages;
+    const int32_t *tokens, *parents;
+};
+
+__global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
+    __shared__ int s_row0[SEV_MAX_BATCH + 1];
+    __shared__ int s_item0[SEV_MAX_BATCH + 1];
+    __shared__ int s_grp0[SEV_MAX_BATCH + 1];
+    const int t = threadIdx.x;
+    const int B = a.B;
+    int my_items = 0, my_groups = 0, my_chunks = 0;
+    if (t < B) {
+        const int slot = a.slot[t], P = a.prefix[t], n = a.nd[t];
+        if (d.seq_len[slot] != P) atomicOr(d.err, 1u);
+        d.pend_n[slot] = 0;                      // a new verify drops whatever was pending
+        d.pend_P[slot] = P;
+        my_groups = (d.G * n + 31) / 32;
+        const int pages = (P + n + SEV_PAGE - 1) / SEV_PAGE;
+        my_chunks = (pages + d.chunk_pages - 1) / d.chunk_pages;
+        my_items = my_groups * my_chunks;
+        s_row0[t + 1] = n;
+        s_item0[t + 1] = my_items;
+        s_grp0[t + 1] = my_groups;
+    }
+    __syncthreads();
+    if (t == 0) {
+        s_row0[0] = s_item0[0] = s_grp0[0] = 0;
+        for (int b = 0; b < B; ++b) {
+            s_row0[b + 1] += s_row0[b];
+            s_item0[b + 1] += s_item0[b];
+            s_grp0[b + 1] += s_grp0[b];
+        }
+    }
+    __syncthreads();
+    if (t < B) {
+        const int slot = a.slot[t], P = a.prefix[t], n = a.nd[t], row0 = s_row0[t];
+        d.p.req_slot[t] = slot;
+        d.p.req_P[t] = P;
+        d.p.req_n[t] = n;
+        d.p.req_row0[t] = row0;
+        if (t == B - 1) d.p.req_row0[B] = s_row0[B];
+        // nodes: parents precede children, so one forward sweep gives depth and ancestor set
+        unsigned long long anc_prev = 0;
+        int depth_prev = -1;
+        for (int i = 0; i < n; ++i) {
+            int par = d.parents ? d.parents[t * a.k_max + i] : i - 1;
+            if (par < -1 || par >= i) { atomicOr(d.err, 2u); par = -1; }
+            unsigned long long anc;
+            int depth;
+            if (par < 0) { anc = 0; depth = 0; }
+            else if (par == i - 1) { anc = anc_prev; depth = depth_prev + 1; }
+            else { anc = d.p.row_anc[row0 + par]; depth = d.p.row_pos[row0 + par] - P + 1; }
+            anc |= 1ull << i;
+            int tok = d.tokens[t * a.k_max + i];
+            if (tok < 0 || tok >= d.vocab) { atomicOr(d.err, 4u); tok = 0; }
+            d.p.row_req[row0 + i] = t;
+            d.p.row_node[row0 + i] = i;
+            d.p.row_pos[row0 + i] = P + depth;
+            d.p.row_anc[row0 + i] = anc;
+            d.p.row_tok[row0 + i] = tok;
+            anc_prev = anc;
+            depth_prev = depth;
+        }
+        // attention work items of this request
+        const int pages = (P + n + SEV_PAGE - 1) / SEV_PAGE;
+        int it = s_item0[t], g0 = s_grp0[t];
+        for (int rg = 0; rg < my_groups; ++rg) {
+            d.p.mg_req[g0 + rg] = t;
+            d.p.mg_rg[g0 + rg] = rg;
+            d.p.mg_item0[g0 + rg] = it;
+            d.p.mg_count[g0 + rg] = my_chunks;
+            for (int c = 0; c < my_chunks; ++c, ++it) {
+                const int p0 = c * d.chunk_pages;
+                d.p.it_req[it] = t;
+                d.p.it_rg[it] = rg;
+                d.p.it_page0[it] = p0;
+                d.p.it_npages[it] = min(d.chunk_pages, pages - p0);
+            }
+        }
+    }
+    __syncthreads();   // row_pos of every row is written (same block)
+    const int rows = s_row0[B], half = d.hd / 2;
+    for (int idx = t; idx < rows * half; idx += blockDim.x) {
+        const int r = idx / half, i = idx - r * half;
+        const double theta = pow(d.rope_base, -2.0 * (double)i / (double)d.hd);
+        double s, c;
+        sincos((double)d.p.row_pos[r] * theta, &s, &c);
+        d.p.row_cs[idx] = make_float2((float)c, (float)s);
+    }
+}
+
+void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_tokens, const int32_t *parents, int rows,
+                 int chunk_pages, hipStream_t st) {
+    (void)rows;
+    PlanDev d;
+    d.p = kv->plan;
+    d.seq_len = kv->seq_len;
+    d.pend_n = kv->pend_n;
+    d.pend_P = kv->pend_P;
+    d.err = kv->err_flags;
+    d.vocab = kv->model->d.vocab;
+    d.hd = kv->model->d.head_dim;
+    d.G = kv->model->d.n_q_heads / kv->model->d.n_kv_heads;
+    d.rope_base = (double)kv->model->d.rope_base;
+    d.chunk_pages = chunk_pages;
+    d.tokens = draft_tokens;
+    d.parents = parents;
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, pa, d);
+}
+
+// ---------------------------------------------------------------------------
+// greedy acceptance (paper section 4.1: accepted candidates plus one additional
+// token from the server's own forward pass).  One thread per request.
+// ---------------------------------------------------------------------------
+__global__ void accept_kernel(DevPlan p, int B, int k_max, int mode, const int32_t *tokens, const int32_t *parents,
+                              const int32_t *row_argmax, const int32_t *next_tok, int32_t *pend_n, int32_t *pend_a,
+                              int32_t *pend_bonus, int32_t *pend_path, int32_t *accept_len, int32_t *bonus_out,
+                              int32_t *path_out) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int slot = p.req_slot[b], n = p.req_n[b], row0 = p.req_row0[b];
+    int32_t *path = pend_path + (size_t)slot * SEV_MAX_DRAFT;
+    int a = 0, want;
+    if (mode == 1) {                       // append: keep the whole chain
+        for (int i = 0; i < n; ++i) path[i] = i;
+        a = n;
+        want = row_argmax[row0 + n - 1];
+    } else {
+        want = next_tok[slot];
+        int cur = -1;
+        while (true) {
+            int nxt = -1;
+            // children of `cur` come after it; the lowest matching index wins
+            for (int c = cur + 1; c < n; ++c) {
+                const int par = parents ? parents[b * k_max + c] : c - 1;
+                const int par_ok = (par < -1 || par >= c) ? -1 : par;
+                if (par_ok == cur && tokens[b * k_max + c] == want) { nxt = c; break; }
+            }
+            if (nxt < 0) break;
+            path[a++] = nxt;
+            cur = nxt;
+            want = row_argmax[row0 + nxt];
+        }
+    }
+    for (int i = a; i < SEV_MAX_DRAFT; ++i) path[i] = -1;
+    pend_n[slot] = n;
+    pend_a[slot] = a;
+    pend_bonus[slot] = want;
+    accept_len[b] = a;
+    bonus_out[b] = want;
+    if (path_out)
+        for (int i = 0; i < k_max; ++i) path_out[b * k_max + i] = i < a ? path[i] : -1;
+}
+
+void launch_accept(const sev_kv *kv, int B, int k_max, int mode, const int32_t *draft_tokens, const int32_t *parents,
+                   int32_t *accept_len, int32_t *bonus, int32_t *accept_path, hipStream_t st) {
+    hipLaunchKernelGGL(accept_kernel, dim3((B + 63) / 64), dim3(64), 0, st, kv->plan, B, k_max, mode, draft_tokens,
+                       parents, kv->row_argmax, kv->next_tok, kv->pend_n, kv->pend_a, kv->pend_bonus, kv->pend_path,
+                       accept_len, bonus, accept_path);
+}
+
+// ---------------------------------------------------------------------------
+// commit / rollback (paper section 4.2: the cache follows the accepted tokens)
+// ---------------------------------------------------------------------------
+struct SlotList {
+    int32_t s[SEV_MAX_BATCH];
+};
+
+// grid (ceil(L*Hkv*hd/256), B).  Each thread owns one (layer, kv head, element) and moves it for the
+// accepted nodes in ascending order; destinations never lie ahead of a source still to be read
+// because an accepted node's index is at least its depth.
+template <typename T, bool BF16>
+__global__ void commit_copy_kernel(SlotList sl, KvGeom g, const int32_t *page_table, int max_pages,
+                                   const int32_t *pend_n, const int32_t *pend_a, const int32_t *pend_P,
+                                   const int32_t *pend_path) {
+    const int slot = sl.s[blockIdx.y];
+    if (pend_n[slot] == 0) return;
+    const int a = pend_a[slot], P = pend_P[slot];
+    const int32_t *path = pend_path + (size_t)slot * SEV_MAX_DRAFT;
+    bool moved = false;
+    for (int j = 0; j < a; ++j) moved |= (path[j] != j);
+    if (!moved) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int per_layer = g.Hkv * g.hd;
+    if (idx >= g.L * per_layer) return;
+    const int layer = idx / per_layer, rem = idx - layer * per_layer, h = rem / g.hd, e = rem - h * g.hd;
+    const int32_t *pt = page_table + (size_t)slot * max_pages;
+    T *base = (T *)(g.pool + (size_t)layer * g.layer_stride);
+    T *vbase = (T *)(g.pool + (size_t)layer * g.layer_stride + g.v_offset);
+    for (int j = 0; j < a; ++j) {
+        const int src = P + path[j], dst = P + j;
+        if (src == dst) continue;
+        const size_t so = (size_t)pt[src / SEV_PAGE] * g.Hkv + h, dofs = (size_t)pt[dst / SEV_PAGE] * g.Hkv + h;
+        const int blk = SEV_PAGE * g.hd;
+        base[dofs * blk + k_in_page<BF16>(dst % SEV_PAGE, e, g.hd)] = base[so * blk + k_in_page<BF16>(src % SEV_PAGE, e, g.hd)];
+        vbase[dofs * blk + v_in_page<BF16>(dst % SEV_PAGE, e, g.hd)] = vbase[so * blk + v_in_page<BF16>(src % SEV_PAGE, e, g.hd)];
+    }
+}
+
+__global__ void commit_state_kernel(SlotList sl, int B, int rollback, int32_t *seq_len, int32_t *next_tok,
+                                    int32_t *pend_n, const int32_t *pend_a, const int32_t *pend_bonus) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int slot = sl.s[b];
+    if (pend_n[slot] == 0) return;
+    if (!rollback) {
+        seq_len[slot] += pend_a[slot];
+        next_tok[slot] = pend_bonus[slot];
+    }
+    pend_n[slot] = 0;
+}
+
+KvGeom sev_kv_geom(const sev_kv *kv);
+
+void launch_commit(const sev_kv *kv, const int32_t *slots, int B, bool rollback, hipStream_t st) {
+    SlotList sl;
+    for (int b = 0; b < B; ++b) sl.s[b] = slots ? slots[b] : b;
+    KvGeom g = sev_kv_geom(kv);
+    if (!rollback) {
+        const int n = g.L * g.Hkv * g.hd;
+        dim3 grid((n + 255) / 256, B);
+        if (kv->model->d.dtype == SEV_BF16)
+            hipLaunchKernelGGL((commit_copy_kernel<uint16_t, true>), grid, dim3(256), 0, st, sl, g, kv->page_table,
+                               kv->max_pages_per_req, kv->pend_n, kv->pend_a, kv->pend_P, kv->pend_path);
+        else
+            hipLaunchKernelGGL((commit_copy_kernel<float, false>), grid, dim3(256), 0, st, sl, g, kv->page_table,
+                               kv->max_pages_per_req, kv->pend_n, kv->pend_a, kv->pend_P, kv->pend_path);
+    }
+    hipLaunchKernelGGL(commit_state_kernel, dim3((B + 63) / 64), dim3(64), 0, st, sl, B, rollback ? 1 : 0, kv->seq_len,
+                       kv->next_tok, kv->pend_n, kv->pend_a, kv->pend_bonus);
+}
+
+// ---------------------------------------------------------------------------
+// cache import / export: plain [n][Hkv][hd] <-> paged layout
+// ---------------------------------------------------------------------------
+template <typename T, bool BF16>
+__global__ void kv_copy_kernel(KvGeom g, const int32_t *pt, int layer, int start, int n, T *k, T *v, int to_cache) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)n * g.Hkv * g.hd;
+    if (idx >= total) return;
+    const int e = (int)(idx % g.hd), h = (int)((idx / g.hd) % g.Hkv), t = (int)(idx / ((int64_t)g.hd * g.Hkv));
+    const int tok = start + t;
+    const size_t blk = (size_t)SEV_PAGE * g.hd;
+    const size_t pb = ((size_t)pt[tok / SEV_PAGE] * g.Hkv + h) * blk;
+    T *kp = (T *)(g.pool + (size_t)layer * g.layer_stride) + pb + k_in_page<BF16>(tok % SEV_PAGE, e, g.hd);
+    T *vp = (T *)(g.pool + (size_t)layer * g.layer_stride + g.v_offset) + pb + v_in_page<BF16>(tok % SEV_PAGE, e, g.hd);
+    if (to_cache) { *kp = k[idx]; *vp = v[idx]; }
+    else { k[idx] = *kp; v[idx] = *vp; }
+}
+
+void launch_kv_copy(const sev_kv *kv, int slot, int layer, int start, int n, void *k, void *v, int to_cache,
+                    hipStream_t st) {
+    KvGeom g = sev_kv_geom(kv);
+    const int64_t total = (int64_t)n * g.Hkv * g.hd;
+    if (total == 0) return;
+    const int32_t *pt = kv->page_table + (size_t)slot * kv->max_pages_per_req;
+    dim3 grid((unsigned)((total + 255) / 256));
+    if (kv->model->d.dtype == SEV_BF16)
+        hipLaunchKernelGGL((kv_copy_kernel<uint16_t, true>), grid, dim3(256), 0, st, g, pt, layer, start, n,
+                           (uint16_t *)k, (uint16_t *)v, to_cache);
+    else
+        hipLaunchKernelGGL((kv_copy_kernel<float, false>), grid, dim3(256), 0, st, g, pt, layer, start, n, (float *)k,
+                           (float *)v, to_cache);
+}
+
+// ---------------------------------------------------------------------------
+// row-wise arg-max over materialised logits (lowest index wins ties)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void argmax_rows_kernel(const float *logits, int vocab, int32_t *out) {
+    __shared__ float sv[256];
+    __shared__ int si[256];
+    const float *row = logits + (size_t)blockIdx.x * vocab;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < vocab; i += 256) {
+        const float v = row[i];
+        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    }
+    sv[threadIdx.x] = bv;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            const float v = sv[threadIdx.x + s];
+            const int i = si[threadIdx.x + s];
+            if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && i < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = i; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = si[0];
+}
+
+void launch_argmax_rows_f32(const float *logits, int rows, int vocab, int32_t *out, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(rows), dim3(256), 0, st, logits, vocab, out);
+}

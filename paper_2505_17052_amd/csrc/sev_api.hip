@@ -1,0 +1,587 @@
+// Host side of libsev: handles, argument validation, weight arena and workspace layout, and the
+// launch sequence of one verification step.  All arithmetic of the method runs in the kernels.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "sev_internal.h"
+#include "kv_layout.h"
+
+// ---------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+int sev_fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+extern "C" const char *sev_last_error(void) { return g_err; }
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------------------
+// model
+// ---------------------------------------------------------------------------
+static int check_desc(const sev_model_desc *d) {
+    if (!d) return sev_fail(SEV_EINVAL, "null model description");
+    if (d->n_layers < 1 || d->d_model < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 2 ||
+        d->d_ffn < 1 || d->vocab < 1)
+        return sev_fail(SEV_EINVAL, "model dimensions must be positive");
+    if (d->n_q_heads % d->n_kv_heads) return sev_fail(SEV_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+    if (d->head_dim % 2) return sev_fail(SEV_EINVAL, "head_dim must be even");
+    if (!(d->rope_base > 1.0f) || !(d->rms_eps >= 0.0f)) return sev_fail(SEV_EINVAL, "bad rope_base / rms_eps");
+    if (d->dtype == SEV_F32) {
+        if (d->head_dim > 256) return sev_fail(SEV_EINVAL, "float32 path supports head_dim <= 256");
+    } else if (d->dtype == SEV_BF16) {
+        if (d->head_dim != 128) return sev_fail(SEV_EINVAL, "bfloat16 path requires head_dim 128");
+        if (d->d_model % 64 || d->d_ffn % 64 || (d->n_q_heads * d->head_dim) % 64)
+            return sev_fail(SEV_EINVAL, "bfloat16 path requires d_model, d_ffn and n_q_heads*head_dim to be multiples of 64");
+        if (d->vocab % 32) return sev_fail(SEV_EINVAL, "bfloat16 path requires vocab to be a multiple of 32");
+        if ((d->n_q_heads / d->n_kv_heads) > 16) return sev_fail(SEV_EINVAL, "at most 16 query heads per KV head");
+    } else {
+        return sev_fail(SEV_EINVAL, "dtype must be SEV_F32 or SEV_BF16");
+    }
+    return SEV_OK;
+}
+
+static size_t layout_model(const sev_model_desc &d, sev_model *m) {
+    const size_t esz = d.dtype == SEV_F32 ? 4 : 2;
+    const size_t q_dim = (size_t)d.n_q_heads * d.head_dim, kv_dim = (size_t)d.n_kv_heads * d.head_dim;
+    const size_t n_qkv = q_dim + 2 * kv_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    size_t off_embed = take((size_t)d.vocab * d.d_model * esz);
+    size_t off_lm = take((size_t)d.vocab * d.d_model * esz);
+    size_t off_gfinal = take((size_t)d.d_model * 4);
+    if (m) {
+        m->off_embed = off_embed;
+        m->off_lm = off_lm;
+        m->off_gfinal = off_gfinal;
+        m->layers.resize(d.n_layers);
+        m->n_qkv = (int)n_qkv;
+        m->q_dim = (int)q_dim;
+        m->kv_dim = (int)kv_dim;
+    }
+    for (int l = 0; l < d.n_layers; ++l) {
+        LayerOffsets lo;
+        lo.wqkv = take(n_qkv * d.d_model * esz);
+        lo.wo = take((size_t)d.d_model * q_dim * esz);
+        lo.wgu = take((size_t)2 * d.d_ffn * d.d_model * esz);
+        lo.wd = take((size_t)d.d_model * d.d_ffn * esz);
+        lo.g_attn = take((size_t)d.d_model * 4);
+        lo.g_ffn = take((size_t)d.d_model * 4);
+        if (m) m->layers[l] = lo;
+    }
+    return off;
+}
+
+extern "C" size_t sev_model_arena_bytes(const sev_model_desc *desc) {
+    if (check_desc(desc) != SEV_OK) return 0;
+    return layout_model(*desc, nullptr);
+}
+
+extern "C" int sev_model_create(const sev_model_desc *desc, void *arena, size_t arena_bytes, sev_model **out) {
+    if (!out) return sev_fail(SEV_EINVAL, "null output handle");
+    *out = nullptr;
+    int rc = check_desc(desc);
+    if (rc) return rc;
+    if (!arena || ((uintptr_t)arena & 255)) return sev_fail(SEV_EINVAL, "arena must be a 256-byte aligned device pointer");
+    sev_model *m = new (std::nothrow) sev_model();
+    if (!m) return sev_fail(SEV_ENOSPACE, "host allocation failed");
+    m->d = *desc;
+    m->arena = (char *)arena;
+    m->arena_bytes = arena_bytes;
+    const size_t need = layout_model(*desc, m);
+    if (arena_bytes < need) {
+        delete m;
+        return sev_fail(SEV_ENOSPACE, "arena too small: %zu < %zu bytes", arena_bytes, need);
+    }
+    launch_fill_f32((float *)(m->arena + m->off_gfinal), 1.0f, desc->d_model, 0);
+    for (int l = 0; l < desc->n_layers; ++l) {
+        launch_fill_f32((float *)(m->arena + m->layers[l].g_attn), 1.0f, desc->d_model, 0);
+        launch_fill_f32((float *)(m->arena + m->layers[l].g_ffn), 1.0f, desc->d_model, 0);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        delete m;
+        return sev_fail(SEV_EHIP, "initialising norm gains: %s", hipGetErrorString(e));
+    }
+    *out = m;
+    return SEV_OK;
+}
+
+extern "C" int sev_model_destroy(sev_model *m) {
+    delete m;
+    return SEV_OK;
+}
+
+extern "C" int sev_model_load_tensor(sev_model *m, int kind, int layer, const void *src, void *stream) {
+    if (!m || !src) return sev_fail(SEV_EINVAL, "null model or source");
+    const sev_model_desc &d = m->d;
+    hipStream_t st = (hipStream_t)stream;
+    const bool per_layer = !(kind == SEV_W_EMBED || kind == SEV_W_LM_HEAD || kind == SEV_W_NORM_FINAL);
+    if (per_layer && (layer < 0 || layer >= d.n_layers)) return sev_fail(SEV_EINVAL, "layer %d out of range", layer);
+    const LayerOffsets *lo = per_layer ? &m->layers[layer] : nullptr;
+    // norm gains: float32 vectors in both precisions
+    if (kind == SEV_W_NORM_ATTN || kind == SEV_W_NORM_FFN || kind == SEV_W_NORM_FINAL) {
+        size_t off = kind == SEV_W_NORM_FINAL ? m->off_gfinal : (kind == SEV_W_NORM_ATTN ? lo->g_attn : lo->g_ffn);
+        launch_pack_f32((float *)(m->arena + off), (const float *)src, d.d_model, st);
+        return SEV_OK;
+    }
+    // destination matrix (possibly a row range of a fused matrix): rows, K, row offset
+    size_t off;
+    int rows, K, row0 = 0, tile_mul = 1, tile_add = 0;
+    switch (kind) {
+    case SEV_W_EMBED: off = m->off_embed; rows = d.vocab; K = d.d_model; break;
+    case SEV_W_LM_HEAD: off = m->off_lm; rows = d.vocab; K = d.d_model; break;
+    case SEV_W_WQ: off = lo->wqkv; rows = m->q_dim; K = d.d_model; break;
+    case SEV_W_WK: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim; break;
+    case SEV_W_WV: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim + m->kv_dim; break;
+    case SEV_W_WO: off = lo->wo; rows = d.d_model; K = m->q_dim; break;
+    // gate and up are interleaved by 32-row tiles in the bf16 layout (tile 2t = gate tile t, 2t+1 = up tile t)
+    case SEV_W_WG: off = lo->wgu; rows = d.d_ffn; K = d.d_model; tile_mul = 2; break;
+    case SEV_W_WU: off = lo->wgu; rows = d.d_ffn; K = d.d_model; tile_mul = 2; tile_add = 1; row0 = d.d_ffn; break;
+    case SEV_W_WD: off = lo->wd; rows = d.d_model; K = d.d_ffn; break;
+    default: return sev_fail(SEV_EINVAL, "unknown tensor kind %d", kind);
+    }
+    if (d.dtype == SEV_F32) {
+        launch_pack_f32((float *)(m->arena + off) + (size_t)row0 * K, (const float *)src, (int64_t)rows * K, st);
+    } else if (kind == SEV_W_EMBED) {
+        SEV_HIP(hipMemcpyAsync(m->arena + off, src, (size_t)rows * K * 2, hipMemcpyDeviceToDevice, st));
+    } else {
+        // bf16 matrices are re-tiled into 32x16 MFMA operand fragments; a row offset inside a fused
+        // matrix is a tile offset (all offsets are multiples of 32 by construction of the shapes)
+        if (rows % 32 || row0 % 32 || K % 16) return sev_fail(SEV_EINVAL, "tensor %d: rows/K not tileable", kind);
+        if (tile_mul == 1) tile_add = row0 / 32;
+        launch_pack_bf16((uint16_t *)(m->arena + off), (const uint16_t *)src, rows, K, tile_mul, tile_add, st);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return sev_fail(SEV_EHIP, "load_tensor: %s", hipGetErrorString(e));
+    return SEV_OK;
+}
+
+// ---------------------------------------------------------------------------
+// KV cache
+// ---------------------------------------------------------------------------
+static size_t kv_block_bytes(const sev_model_desc &d) {
+    return (size_t)SEV_PAGE * d.head_dim * (d.dtype == SEV_F32 ? 4 : 2);
+}
+
+extern "C" size_t sev_kv_pool_bytes(const sev_model *m, int64_t n_pages, int page_size) {
+    if (!m || n_pages < 1 || page_size != SEV_PAGE) return 0;
+    return (size_t)m->d.n_layers * 2 * (size_t)n_pages * m->d.n_kv_heads * kv_block_bytes(m->d);
+}
+
+KvGeom sev_kv_geom(const sev_kv *kv) {
+    KvGeom g;
+    g.pool = kv->pool;
+    g.layer_stride = kv->layer_stride;
+    g.v_offset = kv->v_offset;
+    g.L = kv->model->d.n_layers;
+    g.Hkv = kv->model->d.n_kv_heads;
+    g.hd = kv->model->d.head_dim;
+    return g;
+}
+
+#define ATT_ITEMS_CAP 4096
+
+extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows, int64_t n_pages, int page_size,
+                             void *pool, size_t pool_bytes, sev_kv **out) {
+    if (!out) return sev_fail(SEV_EINVAL, "null output handle");
+    *out = nullptr;
+    if (!m) return sev_fail(SEV_EINVAL, "null model");
+    if (page_size != SEV_PAGE) return sev_fail(SEV_EINVAL, "page_size must be %d", SEV_PAGE);
+    if (max_requests < 1 || max_requests > 65536 || max_rows < 1 || max_rows > (1 << 20) || n_pages < 1 ||
+        n_pages > (1 << 26))
+        return sev_fail(SEV_EINVAL, "max_requests / max_rows / n_pages out of range");
+    if (!pool || ((uintptr_t)pool & 255)) return sev_fail(SEV_EINVAL, "pool must be a 256-byte aligned device pointer");
+    const size_t need = sev_kv_pool_bytes(m, n_pages, page_size);
+    if (pool_bytes < need) return sev_fail(SEV_ENOSPACE, "pool too small: %zu < %zu bytes", pool_bytes, need);
+    sev_kv *kv = new (std::nothrow) sev_kv();
+    if (!kv) return sev_fail(SEV_ENOSPACE, "host allocation failed");
+    const sev_model_desc &d = m->d;
+    kv->model = m;
+    kv->max_req = max_requests;
+    kv->max_rows = max_rows;
+    kv->page_size = page_size;
+    kv->n_pages = n_pages;
+    kv->pool = (char *)pool;
+    kv->pool_bytes = pool_bytes;
+    kv->v_offset = (size_t)n_pages * d.n_kv_heads * kv_block_bytes(d);
+    kv->layer_stride = 2 * kv->v_offset;
+    kv->max_pages_per_req = (int)n_pages;
+    kv->prof_on = 0;
+    memset(kv->prof_ms, 0, sizeof(kv->prof_ms));
+    memset(kv->prof_n, 0, sizeof(kv->prof_n));
+    kv->host_pages.assign(max_requests, 0);
+
+    const bool bf = d.dtype == SEV_BF16;
+    const size_t rows_pad = align_up((size_t)max_rows, 128);
+    const int G = d.n_q_heads / d.n_kv_heads;
+    kv->max_items = bf ? ATT_ITEMS_CAP : 1;
+    kv->max_groups = bf ? (int)(rows_pad * G / 32 + SEV_MAX_BATCH) : 1;
+    const size_t n_qkv = m->n_qkv;
+    kv->part_elems = rows_pad * std::max<size_t>(8 * std::max<size_t>(n_qkv, d.d_model), 2 * (size_t)d.d_ffn);
+
+    // carve the workspace
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    const size_t o_pt = take((size_t)max_requests * kv->max_pages_per_req * 4);
+    const size_t o_seq = take((size_t)max_requests * 4), o_nt = take((size_t)max_requests * 4);
+    const size_t o_pn = take((size_t)max_requests * 4), o_pa = take((size_t)max_requests * 4);
+    const size_t o_pb = take((size_t)max_requests * 4), o_pP = take((size_t)max_requests * 4);
+    const size_t o_pp = take((size_t)max_requests * SEV_MAX_DRAFT * 4);
+    const size_t o_err = take(4);
+    const size_t o_rq = take(4 * (size_t)(SEV_MAX_BATCH + 1) * 4);
+    const size_t o_row = take(4 * rows_pad * 4);
+    const size_t o_anc = take(rows_pad * 8);
+    const size_t o_cs = take(rows_pad * (d.head_dim / 2) * 8);
+    const size_t o_it = take(4 * (size_t)kv->max_items * 4);
+    const size_t o_mg = take(4 * (size_t)kv->max_groups * 4);
+    const size_t o_h = take(rows_pad * d.d_model * 4);
+    const size_t o_part = take(kv->part_elems * 4);
+    const size_t o_xa = take(rows_pad * d.d_model * 4);
+    const size_t o_q = take(rows_pad * n_qkv * 4);
+    const size_t o_o = take(rows_pad * m->q_dim * 4);
+    const size_t o_act = take(rows_pad * d.d_ffn * 4);
+    const size_t o_ao = take(bf ? (size_t)kv->max_items * d.n_kv_heads * 32 * d.head_dim * 4 : 4);
+    const size_t o_ml = take(bf ? (size_t)kv->max_items * d.n_kv_heads * 32 * 8 : 4);
+    const size_t o_lv = take(bf ? (size_t)(d.vocab / 32) * rows_pad * 4 : 4);
+    const size_t o_li = take(bf ? (size_t)(d.vocab / 32) * rows_pad * 4 : 4);
+    const size_t o_am = take(rows_pad * 4);
+    const size_t o_lg = take(bf ? 4 : rows_pad * (size_t)d.vocab * 4);
+    kv->ws_bytes = off;
+    hipError_t e = hipMalloc((void **)&kv->ws, kv->ws_bytes);
+    if (e != hipSuccess) {
+        delete kv;
+        return sev_fail(SEV_EHIP, "workspace allocation of %zu bytes failed: %s", off, hipGetErrorString(e));
+    }
+    e = hipMemset(kv->ws, 0, kv->ws_bytes);
+    if (e != hipSuccess) {
+        hipFree(kv->ws);
+        delete kv;
+        return sev_fail(SEV_EHIP, "workspace clear failed: %s", hipGetErrorString(e));
+    }
+    char *w = kv->ws;
+    kv->page_table = (int32_t *)(w + o_pt);
+    kv->seq_len = (int32_t *)(w + o_seq);
+    kv->next_tok = (int32_t *)(w + o_nt);
+    kv->pend_n = (int32_t *)(w + o_pn);
+    kv->pend_a = (int32_t *)(w + o_pa);
+    kv->pend_bonus = (int32_t *)(w + o_pb);
+    kv->pend_P = (int32_t *)(w + o_pP);
+    kv->pend_path = (int32_t *)(w + o_pp);
+    kv->err_flags = (uint32_t *)(w + o_err);
+    int32_t *rq = (int32_t *)(w + o_rq);
+    kv->plan.req_slot = rq;
+    kv->plan.req_P = rq + (SEV_MAX_BATCH + 1);
+    kv->plan.req_n = rq + 2 * (SEV_MAX_BATCH + 1);
+    kv->plan.req_row0 = rq + 3 * (SEV_MAX_BATCH + 1);
+    int32_t *rw = (int32_t *)(w + o_row);
+    kv->plan.row_req = rw;
+    kv->plan.row_node = rw + rows_pad;
+    kv->plan.row_pos = rw + 2 * rows_pad;
+    kv->plan.row_tok = rw + 3 * rows_pad;
+    kv->plan.row_anc = (unsigned long long *)(w + o_anc);
+    kv->plan.row_cs = (float2 *)(w + o_cs);
+    int32_t *it = (int32_t *)(w + o_it);
+    kv->plan.it_req = it;
+    kv->plan.it_rg = it + kv->max_items;
+    kv->plan.it_page0 = it + 2 * (size_t)kv->max_items;
+    kv->plan.it_npages = it + 3 * (size_t)kv->max_items;
+    int32_t *mg = (int32_t *)(w + o_mg);
+    kv->plan.mg_req = mg;
+    kv->plan.mg_rg = mg + kv->max_groups;
+    kv->plan.mg_item0 = mg + 2 * (size_t)kv->max_groups;
+    kv->plan.mg_count = mg + 3 * (size_t)kv->max_groups;
+    kv->h = (float *)(w + o_h);
+    kv->part = (float *)(w + o_part);
+    kv->xa = w + o_xa;
+    kv->q_buf = w + o_q;
+    kv->o_buf = w + o_o;
+    kv->act = w + o_act;
+    kv->att_o = (float *)(w + o_ao);
+    kv->att_ml = (float2 *)(w + o_ml);
+    kv->lm_val = (float *)(w + o_lv);
+    kv->lm_idx = (int32_t *)(w + o_li);
+    kv->row_argmax = (int32_t *)(w + o_am);
+    kv->logits_f32 = (float *)(w + o_lg);
+    launch_fill_i32(kv->next_tok, -1, max_requests, 0);
+    e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        hipFree(kv->ws);
+        delete kv;
+        return sev_fail(SEV_EHIP, "workspace initialisation failed: %s", hipGetErrorString(e));
+    }
+    *out = kv;
+    return SEV_OK;
+}
+
+extern "C" int sev_kv_destroy(sev_kv *kv) {
+    if (!kv) return SEV_OK;
+    for (auto &s : kv->spans) {
+        hipEventDestroy(s.a);
+        hipEventDestroy(s.b);
+    }
+    hipFree(kv->ws);
+    delete kv;
+    return SEV_OK;
+}
+
+extern "C" int sev_kv_set_pages(sev_kv *kv, int slot, const int32_t *page_ids, int n_pages, void *stream) {
+    if (!kv) return sev_fail(SEV_EINVAL, "null cache");
+    if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "slot %d out of range", slot);
+    if (n_pages < 0 || n_pages > kv->max_pages_per_req || (n_pages && !page_ids))
+        return sev_fail(SEV_EINVAL, "bad page list");
+    for (int i = 0; i < n_pages; ++i)
+        if (page_ids[i] < 0 || page_ids[i] >= kv->n_pages)
+            return sev_fail(SEV_EINVAL, "page id %d out of range at index %d", page_ids[i], i);
+    if (n_pages)
+        SEV_HIP(hipMemcpyAsync(kv->page_table + (size_t)slot * kv->max_pages_per_req, page_ids, (size_t)n_pages * 4,
+                               hipMemcpyHostToDevice, (hipStream_t)stream));
+    kv->host_pages[slot] = n_pages;
+    return SEV_OK;
+}
+
+__global__ void set_state_kernel(int32_t *seq_len, int32_t *next_tok, int32_t *pend_n, int slot, int len, int nt) {
+    seq_len[slot] = len;
+    next_tok[slot] = nt;
+    pend_n[slot] = 0;
+}
+
+extern "C" int sev_kv_set_state(sev_kv *kv, int slot, int32_t seq_len, int32_t next_tok, void *stream) {
+    if (!kv) return sev_fail(SEV_EINVAL, "null cache");
+    if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "slot %d out of range", slot);
+    if (seq_len < 0 || (int64_t)seq_len > (int64_t)kv->host_pages[slot] * SEV_PAGE)
+        return sev_fail(SEV_ENOSPACE, "length %d exceeds the %d pages of slot %d", seq_len, kv->host_pages[slot], slot);
+    if (next_tok < -1 || next_tok >= kv->model->d.vocab) return sev_fail(SEV_EINVAL, "next_tok out of range");
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, kv->seq_len, kv->next_tok, kv->pend_n,
+                       slot, seq_len, next_tok);
+    SEV_HIP(hipGetLastError());
+    return SEV_OK;
+}
+
+extern "C" int sev_kv_get_state(sev_kv *kv, int slot, int32_t *seq_len, int32_t *next_tok, uint32_t *error_flags,
+                                void *stream) {
+    if (!kv) return sev_fail(SEV_EINVAL, "null cache");
+    if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "slot %d out of range", slot);
+    hipStream_t st = (hipStream_t)stream;
+    int32_t a = 0, b = 0;
+    uint32_t f = 0;
+    SEV_HIP(hipMemcpyAsync(&a, kv->seq_len + slot, 4, hipMemcpyDeviceToHost, st));
+    SEV_HIP(hipMemcpyAsync(&b, kv->next_tok + slot, 4, hipMemcpyDeviceToHost, st));
+    SEV_HIP(hipMemcpyAsync(&f, kv->err_flags, 4, hipMemcpyDeviceToHost, st));
+    SEV_HIP(hipStreamSynchronize(st));
+    if (seq_len) *seq_len = a;
+    if (next_tok) *next_tok = b;
+    if (error_flags) *error_flags = f;
+    return SEV_OK;
+}
+
+extern "C" int sev_kv_copy_tokens(sev_kv *kv, int slot, int layer, int start, int n_tokens, void *k, void *v,
+                                  int to_cache, void *stream) {
+    if (!kv || !k || !v) return sev_fail(SEV_EINVAL, "null argument");
+    if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "slot %d out of range", slot);
+    if (layer < 0 || layer >= kv->model->d.n_layers) return sev_fail(SEV_EINVAL, "layer %d out of range", layer);
+    if (start < 0 || n_tokens < 0) return sev_fail(SEV_EINVAL, "negative range");
+    if ((int64_t)start + n_tokens > (int64_t)kv->host_pages[slot] * SEV_PAGE)
+        return sev_fail(SEV_ENOSPACE, "tokens %d..%d exceed the %d pages of slot %d", start, start + n_tokens,
+                        kv->host_pages[slot], slot);
+    launch_kv_copy(kv, slot, layer, start, n_tokens, k, v, to_cache, (hipStream_t)stream);
+    SEV_HIP(hipGetLastError());
+    return SEV_OK;
+}
+
+// ---------------------------------------------------------------------------
+// profiling spans
+// ---------------------------------------------------------------------------
+Prof::Prof(sev_kv *kv_, hipStream_t st_, int cls_) : kv(kv_), st(st_), cls(cls_), a(nullptr), b(nullptr), on(false) {
+    if (!kv->prof_on) return;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+    on = true;
+    hipEventRecord(a, st);
+}
+Prof::~Prof() {
+    if (!on) return;
+    hipEventRecord(b, st);
+    kv->spans.push_back({a, b, cls});
+}
+
+static void prof_collect(sev_kv *kv) {
+    for (auto &s : kv->spans) {
+        hipEventSynchronize(s.b);
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, s.a, s.b) == hipSuccess) {
+            kv->prof_ms[s.cls] += ms;
+            kv->prof_n[s.cls] += 1;
+        }
+        hipEventDestroy(s.a);
+        hipEventDestroy(s.b);
+    }
+    kv->spans.clear();
+}
+
+extern "C" int sev_profile_enable(sev_kv *kv, int on) {
+    if (!kv) return sev_fail(SEV_EINVAL, "null cache");
+    prof_collect(kv);
+    kv->prof_on = on ? 1 : 0;
+    memset(kv->prof_ms, 0, sizeof(kv->prof_ms));
+    memset(kv->prof_n, 0, sizeof(kv->prof_n));
+    return SEV_OK;
+}
+
+extern "C" int sev_profile_read(sev_kv *kv, int which, double *total_ms, int64_t *launches) {
+    if (!kv || which < 0 || which >= PROF_N) return sev_fail(SEV_EINVAL, "bad profile class");
+    prof_collect(kv);
+    if (total_ms) *total_ms = kv->prof_ms[which];
+    if (launches) *launches = kv->prof_n[which];
+    return SEV_OK;
+}
+
+extern "C" const char *sev_profile_name(int which) {
+    static const char *names[PROF_N] = {"gemm_qkv", "gemm_o", "gemm_gate_up_swiglu", "gemm_down", "gemm_lm_head_argmax",
+                                        "attention", "other"};
+    return (which >= 0 && which < PROF_N) ? names[which] : nullptr;
+}
+
+// ---------------------------------------------------------------------------
+// verify
+// ---------------------------------------------------------------------------
+static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, int *n_groups) {
+    const sev_model_desc &d = kv->model->d;
+    const int G = d.n_q_heads / d.n_kv_heads;
+    // aim for a few work items per compute unit, chunks of at least 8 pages, and stay inside the item capacity
+    int64_t total_pages = 0;
+    for (int b = 0; b < pa.B; ++b) total_pages += (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE;
+    int64_t total_groups = 0;
+    for (int b = 0; b < pa.B; ++b) total_groups += (G * pa.nd[b] + 31) / 32;
+    const int64_t want_items = 1024 / std::max(1, d.n_kv_heads);
+    int64_t cp = std::max<int64_t>(8, total_pages * std::max<int64_t>(1, total_groups / pa.B) / std::max<int64_t>(1, want_items));
+    cp = std::min<int64_t>(cp, 64);
+    for (;; cp *= 2) {
+        int64_t items = 0;
+        for (int b = 0; b < pa.B; ++b) {
+            const int64_t pages = (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE;
+            items += ((G * pa.nd[b] + 31) / 32) * ((pages + cp - 1) / cp);
+        }
+        if (items <= kv->max_items) {
+            *n_items = (int)items;
+            *n_groups = (int)total_groups;
+            return (int)cp;
+        }
+        if (cp > (1 << 24)) return -1;
+    }
+}
+
+extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_args *a, void *stream) {
+    if (!m || !kv || !a) return sev_fail(SEV_EINVAL, "null argument");
+    if (kv->model != m) return sev_fail(SEV_EINVAL, "cache was created for another model");
+    if (a->B < 1 || a->B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", a->B, SEV_MAX_BATCH);
+    if (a->k_max < 1 || a->k_max > SEV_MAX_DRAFT) return sev_fail(SEV_EINVAL, "k=%d outside 1..%d", a->k_max, SEV_MAX_DRAFT);
+    if (!a->prefix_lens || !a->draft_tokens || !a->accept_len || !a->bonus_token)
+        return sev_fail(SEV_EINVAL, "prefix_lens, draft_tokens, accept_len and bonus_token are required");
+    if (a->mode != 0 && a->mode != 1) return sev_fail(SEV_EINVAL, "mode must be 0 (verify) or 1 (append)");
+    if (a->mode == 1 && a->parents) return sev_fail(SEV_EINVAL, "append mode takes chains only");
+    PlanArgs pa;
+    pa.B = a->B;
+    pa.k_max = a->k_max;
+    pa.mode = a->mode;
+    int64_t rows = 0;
+    for (int b = 0; b < a->B; ++b) {
+        const int slot = a->slots ? a->slots[b] : b;
+        if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "request %d: slot %d out of range", b, slot);
+        for (int c = 0; c < b; ++c)
+            if (pa.slot[c] == slot) return sev_fail(SEV_EINVAL, "slot %d listed twice", slot);
+        const int n = a->draft_lens ? a->draft_lens[b] : a->k_max;
+        if (n < 1 || n > a->k_max) return sev_fail(SEV_EINVAL, "request %d: draft length %d outside 1..%d", b, n, a->k_max);
+        const int P = a->prefix_lens[b];
+        if (P < 0) return sev_fail(SEV_EINVAL, "request %d: negative prefix length", b);
+        if ((int64_t)P + n > (int64_t)kv->host_pages[slot] * SEV_PAGE)
+            return sev_fail(SEV_ENOSPACE, "request %d: %d+%d tokens exceed the %d pages of slot %d", b, P, n,
+                            kv->host_pages[slot], slot);
+        pa.slot[b] = slot;
+        pa.prefix[b] = P;
+        pa.nd[b] = n;
+        rows += n;
+    }
+    if (rows > kv->max_rows) return sev_fail(SEV_ENOSPACE, "%lld draft tokens exceed max_rows=%d", (long long)rows, kv->max_rows);
+    hipStream_t st = (hipStream_t)stream;
+    int n_items = 0, n_groups = 0, cp = 64;
+    if (m->d.dtype == SEV_BF16) {
+        cp = pick_chunk_pages(kv, pa, &n_items, &n_groups);
+        if (cp < 0) return sev_fail(SEV_ENOSPACE, "attention work list does not fit");
+    }
+    {
+        Prof p(kv, st, PROF_OTHER);
+        launch_plan(kv, pa, a->draft_tokens, a->parents, (int)rows, cp, st);
+    }
+    if (m->d.dtype == SEV_F32) f32_forward(m, kv, (int)rows, a->B, a->logits, st);
+    else bf16_forward(m, kv, (int)rows, a->B, n_items, n_groups, a->logits, st);
+    {
+        Prof p(kv, st, PROF_OTHER);
+        launch_accept(kv, a->B, a->k_max, a->mode, a->draft_tokens, a->parents, a->accept_len, a->bonus_token,
+                      a->accept_path, st);
+        if (a->row_argmax)
+            SEV_HIP(hipMemcpyAsync(a->row_argmax, kv->row_argmax, (size_t)rows * 4, hipMemcpyDeviceToDevice, st));
+    }
+    SEV_HIP(hipGetLastError());
+    return SEV_OK;
+}
+
+extern "C" int sev_verify(const sev_model *weights, sev_kv *kv_cache, const int32_t *prefix_lens,
+                          const int32_t *draft_tokens, const int32_t *draft_mask, int B, int k, int32_t *accept_len,
+                          int32_t *bonus_token, void *stream) {
+    sev_verify_args a;
+    memset(&a, 0, sizeof(a));
+    a.B = B;
+    a.k_max = k;
+    a.prefix_lens = prefix_lens;
+    a.draft_tokens = draft_tokens;
+    a.parents = draft_mask;
+    a.accept_len = accept_len;
+    a.bonus_token = bonus_token;
+    return sev_verify_ex(weights, kv_cache, &a, stream);
+}
+
+static int check_slots(sev_kv *kv, const int32_t *slots, int B) {
+    if (!kv) return sev_fail(SEV_EINVAL, "null cache");
+    if (B < 1 || B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", B, SEV_MAX_BATCH);
+    for (int b = 0; b < B; ++b) {
+        const int s = slots ? slots[b] : b;
+        if (s < 0 || s >= kv->max_req) return sev_fail(SEV_EINVAL, "slot %d out of range", s);
+    }
+    return SEV_OK;
+}
+
+extern "C" int sev_kv_commit(sev_kv *kv, const int32_t *slots, int B, void *stream) {
+    int rc = check_slots(kv, slots, B);
+    if (rc) return rc;
+    Prof p(kv, (hipStream_t)stream, PROF_OTHER);
+    launch_commit(kv, slots, B, false, (hipStream_t)stream);
+    SEV_HIP(hipGetLastError());
+    return SEV_OK;
+}
+
+extern "C" int sev_kv_rollback(sev_kv *kv, const int32_t *slots, int B, void *stream) {
+    int rc = check_slots(kv, slots, B);
+    if (rc) return rc;
+    launch_commit(kv, slots, B, true, (hipStream_t)stream);
+    SEV_HIP(hipGetLastError());
+    return SEV_OK;
+}

@@ -1,0 +1,155 @@
+// Internal declarations shared by the translation units of libsev.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <vector>
+
+#include "../../include/sev.h"
+
+#define SEV_PAGE 16
+
+// ---------------------------------------------------------------------------
+// error plumbing (host)
+// ---------------------------------------------------------------------------
+int sev_fail(int code, const char *fmt, ...);
+#define SEV_HIP(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess)                                                              \
+            return sev_fail(SEV_EHIP, "%s: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+// ---------------------------------------------------------------------------
+// packed activation layout for the matrix-core GEMMs ("xpack")
+//
+// A [M][K] activation matrix is carried as two bf16 planes (hi = bf16(x),
+// lo = bf16(x - hi)), already arranged as MFMA 32x32x16 operand fragments:
+//   [K/16 k-steps][m_tiles][plane 2][lane 64][8 bf16]
+// lane = (m % 32) + 32 * ((k / 8) % 2), element = k % 8.  One fragment is 1 KiB.
+// m_tiles is ceil(M/32) rounded up to a multiple of 4.
+// ---------------------------------------------------------------------------
+__host__ __device__ inline int64_t xpack_index(int m, int k, int plane, int m_tiles) {
+    return ((((int64_t)(k >> 4) * m_tiles + (m >> 5)) * 2 + plane) << 9) + (((m & 31) + (((k >> 3) & 1) << 5)) << 3) +
+           (k & 7);
+}
+
+struct LayerOffsets {
+    size_t wqkv, wo, wgu, wd, g_attn, g_ffn;
+};
+
+struct sev_model {
+    sev_model_desc d;
+    char *arena;
+    size_t arena_bytes;
+    size_t off_embed, off_lm, off_gfinal;
+    std::vector<LayerOffsets> layers;
+    int n_qkv;   // (Hq + 2 Hkv) * hd
+    int q_dim;   // Hq * hd
+    int kv_dim;  // Hkv * hd
+};
+
+// Per-call description handed to the plan kernel by value.
+struct PlanArgs {
+    int B, k_max, mode;
+    int32_t slot[SEV_MAX_BATCH];
+    int32_t prefix[SEV_MAX_BATCH];
+    int32_t nd[SEV_MAX_BATCH];
+};
+
+// Device-side call plan (one per sev_kv; rebuilt by every verify).
+struct DevPlan {
+    // per request
+    int32_t *req_slot, *req_P, *req_n, *req_row0;
+    // per row (draft node)
+    int32_t *row_req, *row_node, *row_pos, *row_tok;
+    unsigned long long *row_anc;
+    float2 *row_cs;           // [rows][hd/2] (cos, sin) of pos * theta_i
+    // attention work items (bf16 path)
+    int32_t *it_req, *it_rg, *it_page0, *it_npages;        // [items]
+    int32_t *mg_req, *mg_rg, *mg_item0, *mg_count;         // [merge groups]
+};
+
+enum ProfClass { PROF_GEMM_QKV = 0, PROF_GEMM_O, PROF_GEMM_GU, PROF_GEMM_DOWN, PROF_GEMM_LM, PROF_ATTN, PROF_OTHER, PROF_N };
+
+struct ProfSpan {
+    hipEvent_t a, b;
+    int cls;
+};
+
+struct sev_kv {
+    const sev_model *model;
+    int max_req, max_rows, page_size;
+    int64_t n_pages;
+    char *pool;
+    size_t pool_bytes;
+    size_t layer_stride;      // bytes between layers in the pool
+    size_t v_offset;          // bytes from a layer's K pages to its V pages
+    int max_pages_per_req;
+
+    // device state (one allocation: `ws`)
+    char *ws;
+    size_t ws_bytes;
+    int32_t *page_table;      // [max_req][max_pages_per_req]
+    int32_t *seq_len, *next_tok;             // [max_req]
+    int32_t *pend_n, *pend_a, *pend_bonus, *pend_P;   // [max_req] pending block: size, accepted, bonus, prefix length at verify
+    int32_t *pend_path;       // [max_req][SEV_MAX_DRAFT]
+    uint32_t *err_flags;      // [1]
+    DevPlan plan;
+    int max_items, max_groups;
+
+    // activations
+    float *h;                 // [rows][d] residual stream
+    float *part;              // split-K partial sums / f32 scratch
+    size_t part_elems;
+    void *xa;                 // normed activations (xpack for bf16, [rows][d] f32 otherwise)
+    void *q_buf;              // bf16: q hi/lo planes [2][rows][Hq*hd]; f32: qkv [rows][n_qkv]
+    void *o_buf;              // attention output (xpack K=q_dim, or f32 [rows][q_dim])
+    void *act;                // SwiGLU output (xpack K=d_ffn, or f32 [rows][d_ffn])
+    float *att_o;             // attention partials [items*Hkv][32][hd]
+    float2 *att_ml;           // [items*Hkv][32] (running max, sum)
+    float *lm_val;            // [tiles][rows] partial arg-max values
+    int32_t *lm_idx;
+    int32_t *row_argmax;      // [rows]
+    float *logits_f32;        // f32 path only: [rows][vocab]
+
+    // host mirrors
+    std::vector<int> host_pages;   // pages assigned per slot
+    // profiling
+    int prof_on;
+    std::vector<ProfSpan> spans;
+    double prof_ms[PROF_N];
+    int64_t prof_n[PROF_N];
+};
+
+struct Prof {
+    sev_kv *kv;
+    hipStream_t st;
+    int cls;
+    hipEvent_t a, b;
+    bool on;
+    Prof(sev_kv *kv_, hipStream_t st_, int cls_);
+    ~Prof();
+};
+
+// ---------------------------------------------------------------------------
+// launchers (defined in the kernel translation units)
+// ---------------------------------------------------------------------------
+// common
+void launch_fill_f32(float *p, float v, int64_t n, hipStream_t st);
+void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st);
+void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_tokens, const int32_t *parents, int rows,
+                 int chunk_pages, hipStream_t st);
+void launch_accept(const sev_kv *kv, int B, int k_max, int mode, const int32_t *draft_tokens, const int32_t *parents,
+                   int32_t *accept_len, int32_t *bonus, int32_t *accept_path, hipStream_t st);
+void launch_commit(const sev_kv *kv, const int32_t *slots_dev_by_value, int B, bool rollback, hipStream_t st);
+void launch_kv_copy(const sev_kv *kv, int slot, int layer, int start, int n, void *k, void *v, int to_cache, hipStream_t st);
+void launch_argmax_rows_f32(const float *logits, int rows, int vocab, int32_t *out, hipStream_t st);
+
+// f32 path
+void launch_pack_f32(float *dst, const float *src, int64_t n, hipStream_t st);
+void f32_forward(const sev_model *m, sev_kv *kv, int rows, int B, float *logits_out, hipStream_t st);
+
+// bf16 path
+void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int tile_mul, int tile_add, hipStream_t st);
+void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, float *logits_out,
+                  hipStream_t st);

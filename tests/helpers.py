@@ -21,3 +21,14 @@ def corrupt_chain(greedy: np.ndarray, req: synth.workload.Request, n: int) -> np
         if req.corrupt_draw[j] < req.corrupt_p:
             d[j] = req.random_tokens[j]
     return d
+
+
+def decision_gap_ok(res, gap_min: float) -> bool:
+    """True iff every arg-max the oracle's acceptance walk relied on (the nodes of its accepted path;
+    the last of them also produced the stop decision and the bonus token) has a top-1/top-2 logit gap
+    of at least gap_min.  Only such requests are compared bit-exactly."""
+    return all(res.top2_gap[i] >= gap_min for i in res.path)
+
+
+def announce(msg: str):
+    print(f"[case] {msg}", flush=True)
