@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsev.so")
-SOURCES = ["sev_api.hip", "kernels_common.hip", "kernels_f32.hip", "kernels_bf16_stub.hip"]
+SOURCES = ["sev_api.hip", "kernels_common.hip", "kernels_f32.hip", "kernels_bf16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result"]
 

@@ -1,0 +1,781 @@
+// bfloat16 path for gfx950: matrix-core GEMMs that stream re-tiled bf16 weights once per step,
+// paged-KV verification attention, and the fused element-wise stages between them.
+//
+// Precision recipe.  Weights and the KV cache are bf16.  Every activation that feeds a matrix
+// core is carried as TWO bf16 planes, hi = bf16(x) and lo = bf16(x - hi), and multiplied in two
+// MFMAs that accumulate into the same float32 registers; the residual stream, norms, rotary
+// embedding, softmax and all accumulations are float32.  (A single bf16 plane per activation
+// accumulates ~3 % relative error over 32 layers; the split keeps it near 1e-5.)
+#include <string.h>
+
+#include <algorithm>
+
+#include "sev_internal.h"
+#include "kv_layout.h"
+
+KvGeom sev_kv_geom(const sev_kv *kv);
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;          // round to nearest even (finite inputs)
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// hi/lo split of one float: hi = bf16(x), lo = bf16(x - hi)
+__device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) {
+    hi = f32_to_bf16_bits(x);
+    lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
+}
+
+// Writes 8 consecutive-k activations of row m (k0 a multiple of 8) as hi and lo fragments.
+__device__ __forceinline__ void store_split8(uint16_t *xp, int m, int k0, int m_tiles, const float *v) {
+    uint32_t h[8], l[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) split_bf16(v[i], h[i], l[i]);
+    uint4 H = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    uint4 Lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+    *(uint4 *)(xp + xpack_index(m, k0, 0, m_tiles)) = H;
+    *(uint4 *)(xp + xpack_index(m, k0, 1, m_tiles)) = Lo;
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ float block_sum_256(float v, float *red) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const float s = red[0] + red[1] + red[2] + red[3];
+    __syncthreads();
+    return s;
+}
+
+// ---------------------------------------------------------------------------
+// weight re-tiling: canonical [rows][K] bf16 -> [tile][K/16][lane 64][8], where lane
+// (n % 32) + 32*((k/8)%2) holds W[n][k..k+7]: exactly the A operand of a 32x32x16 MFMA.
+// Source tile t lands at destination tile t*tile_mul + tile_add (gate/up interleave, fused QKV).
+// ---------------------------------------------------------------------------
+__global__ void pack_bf16_kernel(uint4 *dst, const uint16_t *src, int K, int64_t n_chunks, int tile_mul, int tile_add) {
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= n_chunks) return;
+    const int ksteps = K >> 4;
+    const int lane = (int)(c & 63);
+    const int64_t tk = c >> 6;
+    const int kt = (int)(tk % ksteps);
+    const int64_t t = tk / ksteps;
+    const int64_t n = t * 32 + (lane & 31);
+    const int k = kt * 16 + 8 * (lane >> 5);
+    const uint4 v = *(const uint4 *)(src + n * K + k);
+    dst[((t * tile_mul + tile_add) * ksteps + kt) * 64 + lane] = v;
+}
+
+void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int tile_mul, int tile_add, hipStream_t st) {
+    const int64_t n_chunks = (int64_t)(n_rows / 32) * (K / 16) * 64;
+    hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, (uint4 *)dst, src,
+                       K, n_chunks, tile_mul, tile_add);
+}
+
+// ---------------------------------------------------------------------------
+// embedding gather + first RMSNorm.  One block per row.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, const int32_t *row_tok, const float *g,
+                                                         float *h, uint16_t *xa, int d, int m_tiles, float eps) {
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    const uint16_t *src = E + (size_t)row_tok[m] * d;
+    float *hr = h + (size_t)m * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d / 8; c += 256) {
+        const uint4 raw = *(const uint4 *)(src + c * 8);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = bf16_bits_to_f32(w[i] & 0xffffu);
+            v[2 * i + 1] = bf16_bits_to_f32(w[i] >> 16);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ss += v[i] * v[i];
+        *(float4 *)(hr + c * 8) = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4 *)(hr + c * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    ss = block_sum_256(ss, red);
+    const float r = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c = threadIdx.x; c < d / 8; c += 256) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = hr[c * 8 + i] * r * g[c * 8 + i];
+        store_split8(xa, m, c * 8, m_tiles, v);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// residual add of split-K partial sums + RMSNorm of the updated stream.  One block per row.
+//   h[m] += sum_s part[s][m]   (fixed order)        xa = split(rmsnorm(h[m]) * g)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void resid_norm_kernel(float *h, const float *part, int S, int M, const float *g,
+                                                         uint16_t *xa, int d, int m_tiles, float eps) {
+    __shared__ float red[4];
+    const int m = blockIdx.x;
+    float *hr = h + (size_t)m * d;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < d / 4; c += 256) {
+        float4 a = *(float4 *)(hr + c * 4);
+        for (int s = 0; s < S; ++s) {
+            const float4 p = *(const float4 *)(part + ((size_t)s * M + m) * d + c * 4);
+            a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+        }
+        *(float4 *)(hr + c * 4) = a;
+        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+    }
+    ss = block_sum_256(ss, red);        // also orders the writes of h before the reads below
+    const float r = 1.0f / sqrtf(ss / (float)d + eps);
+    for (int c = threadIdx.x; c < d / 8; c += 256) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = hr[c * 8 + i] * r * g[c * 8 + i];
+        store_split8(xa, m, c * 8, m_tiles, v);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// skinny-M GEMM on the matrix cores:  Y[M][N] = X[M][K] * W[N][K]^T
+//
+// A block of 4 waves covers up to 128 rows (MT tiles of 32) and 4*NT column tiles of 32; wave w
+// owns NT column tiles.  Weights go global -> registers, one fully coalesced 1 KiB fragment per
+// load, PF stages ahead; each weight byte is read once per 128 rows.  Activations (hi and lo
+// planes, already in fragment order) go global -> LDS once per block and are shared by the 4 waves.
+// MFMA 32x32x16: A = weight tile (32 n x 16 k), B = activation tile (16 k x 32 m), so a lane ends up
+// with 4 consecutive output columns of one row per register quad (vector stores along N).
+// grid: x = column groups, y = split-K slices, z = blocks of 128 rows.
+// ---------------------------------------------------------------------------
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
+
+struct GemmArgs {
+    const uint4 *W;          // re-tiled weights
+    const uint4 *X;          // xpack activations
+    int n_tiles, k_steps, m_tiles_total, M, N;
+    float *part;             // EPI_PARTIAL: [S][M][N]
+    uint16_t *act;           // EPI_SWIGLU: xpack with K = N/2
+    float *lm_val;           // EPI_ARGMAX: [gridDim.x*4][lm_stride]
+    int32_t *lm_idx;
+    int lm_stride;
+    float *logits;           // EPI_ARGMAX, optional: [M][N]
+};
+
+template <int MT, int NT, int EPI, int PF>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+    extern __shared__ uint4 xs[];                       // [2 buffers][2 k-steps][MT][2 planes][64 lanes]
+    constexpr int STAGE_U4 = 2 * MT * 2 * 64;           // uint4 per stage
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tile0 = (blockIdx.x * 4 + wave) * NT;
+    const int mt0 = blockIdx.z * 4;
+    const int n_stages = g.k_steps >> 1;
+    const int s_begin = (int)((int64_t)n_stages * blockIdx.y / gridDim.y);
+    const int s_end = (int)((int64_t)n_stages * (blockIdx.y + 1) / gridDim.y);
+    const int n = s_end - s_begin;
+
+    f32x16 acc[NT][MT];
+#pragma unroll
+    for (int a = 0; a < NT; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    // weight fragment pointers of this lane (clamped to a valid tile so idle waves load harmlessly)
+    const uint4 *wp[NT];
+#pragma unroll
+    for (int a = 0; a < NT; ++a) {
+        const int t = min(tile0 + a, g.n_tiles - 1);
+        wp[a] = g.W + ((size_t)t * g.k_steps) * 64 + lane;
+    }
+    uint4 wreg[PF][NT][2];
+    uint4 x0, x1, x2, x3;                               // activation staging (scalars: MT <= 4 are used)
+    x0 = x1 = x2 = x3 = make_uint4(0, 0, 0, 0);
+
+    auto load_w = [&](int u, int st) {
+#pragma unroll
+        for (int a = 0; a < NT; ++a)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = wp[a][(size_t)(2 * st + ks) * 64];
+    };
+    // the stage's activation fragments are MT*256 consecutive 16-byte units per k-step pair
+    auto x_src = [&](int st, int i) -> const uint4 * {
+        const int u = threadIdx.x + 256 * i;
+        const int ksl = u / (MT * 128), within = u - ksl * (MT * 128);
+        return g.X + ((size_t)(2 * st + ksl) * g.m_tiles_total + mt0) * 128 + within;
+    };
+    auto load_x = [&](int st) {
+        x0 = *x_src(st, 0);
+        if constexpr (MT > 1) x1 = *x_src(st, 1);
+        if constexpr (MT > 2) { x2 = *x_src(st, 2); x3 = *x_src(st, 3); }
+    };
+    auto store_x = [&](int buf) {
+        uint4 *dst = xs + buf * STAGE_U4 + threadIdx.x;
+        dst[0] = x0;
+        if constexpr (MT > 1) dst[256] = x1;
+        if constexpr (MT > 2) { dst[512] = x2; dst[768] = x3; }
+    };
+
+    // Prologue: PF weight stages in flight, first activation stage in LDS.  Stage indices past the
+    // slice end are clamped (a redundant, cached re-load) so the pipeline body stays branch-free.
+    const int s_last = s_end - 1;
+#pragma unroll
+    for (int u = 0; u < PF; ++u) load_w(u, min(s_begin + u, s_last));
+    load_x(s_begin);
+    store_x(0);
+    __syncthreads();
+
+    for (int base = 0; base < n; base += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int st = base + u;
+            if (st < n) {                                  // block-uniform
+                load_x(min(s_begin + st + 1, s_last));
+                const uint4 *xb = xs + (u & 1) * STAGE_U4;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+                    for (int b = 0; b < MT; ++b) {
+                        const bf16x8 xh = as_bf16x8(xb[((ks * MT + b) * 2 + 0) * 64 + lane]);
+                        const bf16x8 xl = as_bf16x8(xb[((ks * MT + b) * 2 + 1) * 64 + lane]);
+#pragma unroll
+                        for (int a = 0; a < NT; ++a) {
+                            const bf16x8 w = as_bf16x8(wreg[u][a][ks]);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, xh, acc[a][b], 0, 0, 0);
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, xl, acc[a][b], 0, 0, 0);
+                        }
+                    }
+                }
+                load_w(u, min(s_begin + st + PF, s_last));
+                store_x((u + 1) & 1);
+                __syncthreads();
+            }
+        }
+    }
+
+    // ------------------------------------------------------------------ epilogues
+    const int mrow = lane & 31, nsub = 4 * (lane >> 5);
+    if constexpr (EPI == EPI_PARTIAL) {
+        float *out = g.part + (size_t)blockIdx.y * g.M * g.N;
+#pragma unroll
+        for (int a = 0; a < NT; ++a) {
+            if (tile0 + a >= g.n_tiles) continue;
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+                const int m = (mt0 + b) * 32 + mrow;
+                if (m >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int nn = (tile0 + a) * 32 + 8 * j + nsub;
+                    *(float4 *)(out + (size_t)m * g.N + nn) =
+                        make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+                }
+            }
+        }
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // tile pair (2t, 2t+1) = (gate tile t, up tile t)
+        if (tile0 + 1 < g.n_tiles) {
+            const int tp = tile0 >> 1;
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+                const int m = (mt0 + b) * 32 + mrow;
+                if (m >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t hi[4], lo[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float gt = acc[0][b][4 * j + r], up = acc[NT - 1][b][4 * j + r];
+                        const float v = gt / (1.0f + __expf(-gt)) * up;
+                        split_bf16(v, hi[r], lo[r]);
+                    }
+                    const int f0 = tp * 32 + 8 * j + nsub;
+                    *(uint2 *)(g.act + xpack_index(m, f0, 0, g.m_tiles_total)) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+                    *(uint2 *)(g.act + xpack_index(m, f0, 1, g.m_tiles_total)) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+                }
+            }
+        }
+    } else {
+        // arg-max over this wave's columns for every row (lowest index wins ties)
+#pragma unroll
+        for (int b = 0; b < MT; ++b) {
+            const int m = (mt0 + b) * 32 + mrow;
+            float bv = -INFINITY;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int a = 0; a < NT; ++a) {
+                if (tile0 + a >= g.n_tiles) continue;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int nn = (tile0 + a) * 32 + 8 * j + nsub;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float v = acc[a][b][4 * j + r];
+                        if (v > bv) { bv = v; bi = nn + r; }       // indices ascend, so ">" keeps the lowest
+                    }
+                    if (g.logits && m < g.M)
+                        *(float4 *)(g.logits + (size_t)m * g.N + nn) =
+                            make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+                }
+            }
+            const float ov = __shfl_xor(bv, 32);
+            const int oi = __shfl_xor(bi, 32);
+            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            if (lane < 32 && m < g.M) {
+                const size_t slot = (size_t)(blockIdx.x * 4 + wave) * g.lm_stride + m;
+                g.lm_val[slot] = bv;
+                g.lm_idx[slot] = bi;
+            }
+        }
+    }
+}
+
+// final arg-max over the per-wave partial results of the LM-head GEMM; one block per row
+__global__ __launch_bounds__(256) void lm_reduce_kernel(const float *val, const int32_t *idx, int n_part, int stride,
+                                                        int32_t *out) {
+    __shared__ float sv[256];
+    __shared__ int si[256];
+    const int m = blockIdx.x;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int p = threadIdx.x; p < n_part; p += 256) {
+        const float v = val[(size_t)p * stride + m];
+        const int i = idx[(size_t)p * stride + m];
+        if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+    }
+    sv[threadIdx.x] = bv;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            const float v = sv[threadIdx.x + s];
+            const int i = si[threadIdx.x + s];
+            if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && i < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = i; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[m] = si[0];
+}
+
+// ---------------------------------------------------------------------------
+// QKV post-processing: sum split-K partials, rotate q and k, write q as hi/lo planes for the
+// attention kernel and append k, v (bf16) to the paged cache at position P + node.
+// grid (rows, Hq + Hkv), 64 threads: thread i owns the rotary pair (i, i + 64).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void rope_kv_bf16_kernel(const float *part, int S, int M, int n_qkv, DevPlan p, KvGeom g,
+                                                          const int32_t *page_table, int max_pages, int layer, int Hq,
+                                                          uint16_t *q_planes) {
+    const int m = blockIdx.x, hy = blockIdx.y, i = threadIdx.x;
+    const float2 cs = p.row_cs[(size_t)m * 64 + i];
+    const int col = (hy < Hq ? hy * 128 : Hq * 128 + (hy - Hq) * 128);
+    float a = 0.f, b = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const float *r = part + ((size_t)s * M + m) * n_qkv + col;
+        a += r[i];
+        b += r[i + 64];
+    }
+    if (hy < Hq) {
+        const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
+        uint32_t h0, l0, h1, l1;
+        split_bf16(ra, h0, l0);
+        split_bf16(rb, h1, l1);
+        const size_t qd = (size_t)Hq * 128, o = (size_t)m * qd + hy * 128;
+        q_planes[o + i] = (uint16_t)h0;
+        q_planes[o + i + 64] = (uint16_t)h1;
+        q_planes[(size_t)M * qd + o + i] = (uint16_t)l0;
+        q_planes[(size_t)M * qd + o + i + 64] = (uint16_t)l1;
+        return;
+    }
+    const int h = hy - Hq, rb_ = p.row_req[m];
+    const int tok = p.req_P[rb_] + p.row_node[m], slot = p.req_slot[rb_];
+    const size_t pb = ((size_t)page_table[(size_t)slot * max_pages + tok / SEV_PAGE] * g.Hkv + h) * (SEV_PAGE * 128);
+    uint16_t *kc = (uint16_t *)(g.pool + (size_t)layer * g.layer_stride) + pb;
+    uint16_t *vc = (uint16_t *)(g.pool + (size_t)layer * g.layer_stride + g.v_offset) + pb;
+    const int t = tok % SEV_PAGE;
+    kc[k_in_page<true>(t, i, 128)] = (uint16_t)f32_to_bf16_bits(a * cs.x - b * cs.y);
+    kc[k_in_page<true>(t, i + 64, 128)] = (uint16_t)f32_to_bf16_bits(b * cs.x + a * cs.y);
+    // v columns follow the k columns of all KV heads
+    float va = 0.f, vb = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const float *r = part + ((size_t)s * M + m) * n_qkv + col + g.Hkv * 128;
+        va += r[i];
+        vb += r[i + 64];
+    }
+    vc[v_in_page<true>(t, i, 128)] = (uint16_t)f32_to_bf16_bits(va);
+    vc[v_in_page<true>(t, i + 64, 128)] = (uint16_t)f32_to_bf16_bits(vb);
+}
+
+// ---------------------------------------------------------------------------
+// verification attention over the paged bf16 cache (head_dim 128, 16-token pages).
+//
+// Work item = (request, group of 32 query rows, KV chunk) x KV head.  The 32 rows are
+// (query head in the GQA group) x (draft node), so every K/V byte is read once for the whole
+// group.  The 4 waves of a block take alternate page pairs of the chunk; each wave runs
+//   S^T = K Q^T   : MFMA 16x16x32, A = one page of keys (16 keys x 32 dims: one coalesced 1 KiB
+//                   load thanks to the in-page layout), B = q (hi and lo planes)
+//   O^T += V^T P^T: MFMA 16x16x32 over a pair of pages; the S^T register layout IS the B-operand
+//                   layout of P^T, so probabilities never leave registers
+// with an online softmax per query row; then the waves' partial (max, sum, O) are merged through
+// LDS and written out for the cross-chunk merge.  Masking: keys < P are visible to every row;
+// key P + j is visible to a row iff bit j of the row's ancestor mask is set.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g,
+                                                        const int32_t *page_table, int max_pages, int layer, int Hq,
+                                                        float *att_o, float2 *att_ml, float scale_log2e) {
+    extern __shared__ float lds[];                    // two merge slots: 64 accumulator registers + max + sum per lane
+    const int item = blockIdx.x, kvh = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int b = p.it_req[item], rg = p.it_rg[item], page0 = p.it_page0[item], npages = p.it_npages[item];
+    const int P = p.req_P[b], n = p.req_n[b], row0 = p.req_row0[b], slot = p.req_slot[b];
+    const int G = Hq / g.Hkv;
+    const int qi = lane & 15, grp = lane >> 4;
+    const int32_t *pt = page_table + (size_t)slot * max_pages;
+    const char *Kl = g.pool + (size_t)layer * g.layer_stride;
+    const char *Vl = Kl + g.v_offset;
+    const size_t qd = (size_t)Hq * 128;
+
+    // query fragments (B operand: lane (q = lane%16, c = lane/16) holds dims 32*step + 8c .. +7)
+    bf16x8 qf[2][2][4];
+    unsigned long long anc[2];
+    bool rvalid[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const int R = rg * 32 + qt * 16 + qi;
+        rvalid[qt] = R < G * n;
+        const int hg = rvalid[qt] ? R / n : 0, node = rvalid[qt] ? R - hg * n : 0;
+        const int m = row0 + node;
+        anc[qt] = rvalid[qt] ? p.row_anc[m] : 0ull;
+        const size_t o = (size_t)m * qd + (size_t)(kvh * G + hg) * 128 + 8 * grp;
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (rvalid[qt]) v = *(const uint4 *)(q_planes + (size_t)pl * M * qd + o + 32 * st);
+                qf[pl][qt][st] = as_bf16x8(v);
+            }
+    }
+
+    f32x4 oacc[8][2];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) oacc[t][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
+
+    const int npairs = (npages + 1) >> 1;
+    for (int pp = wave; pp < npairs; pp += 4) {
+        const int lp0 = page0 + 2 * pp;                     // logical pages of the pair
+        const bool has1 = (2 * pp + 1) < npages;
+        const size_t blk0 = ((size_t)pt[lp0] * g.Hkv + kvh) * 4096;
+        const size_t blk1 = ((size_t)pt[has1 ? lp0 + 1 : lp0] * g.Hkv + kvh) * 4096;
+        uint4 k0[4], k1[4], v0[4], v1[4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            k0[st] = *(const uint4 *)(Kl + blk0 + st * 1024 + lane * 16);
+            k1[st] = *(const uint4 *)(Kl + blk1 + st * 1024 + lane * 16);
+        }
+#pragma unroll
+        for (int tp = 0; tp < 4; ++tp) {
+            v0[tp] = *(const uint4 *)(Vl + blk0 + tp * 1024 + lane * 16);
+            v1[tp] = *(const uint4 *)(Vl + blk1 + tp * 1024 + lane * 16);
+        }
+        // scores: s[page][qt] holds keys 4*grp + r of the page for query qi
+        f32x4 s[2][2];
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int st = 0; st < 4; ++st) {
+                    const bf16x8 kf = as_bf16x8(pg ? k1[st] : k0[st]);
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[0][qt][st], a, 0, 0, 0);
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[1][qt][st], a, 0, 0, 0);
+                }
+                s[pg][qt] = a;
+            }
+        const int key0 = lp0 * 16 + 4 * grp;                // first key of this lane in page 0 of the pair
+        const bool need_mask = (lp0 + 2) * 16 > P || !has1;
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = s[pg][qt][r] * scale_log2e;
+                    if (need_mask) {
+                        const int key = key0 + pg * 16 + r;
+                        bool vis = key < P || (key - P < n && ((anc[qt] >> (key - P)) & 1ull));
+                        if (pg && !has1) vis = false;
+                        if (!vis) v = -INFINITY;
+                    }
+                    s[pg][qt][r] = v;
+                    mx = fmaxf(mx, v);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float mnew = fmaxf(mrun[qt], mx);
+            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            const float alpha = exp2f(mrun[qt] - muse);
+            mrun[qt] = mnew;
+            float ps = 0.f;
+            uint32_t ph[8], plo[8];
+#pragma unroll
+            for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pv = exp2f(s[pg][qt][r] - muse);
+                    ps += pv;
+                    split_bf16(pv, ph[pg * 4 + r], plo[pg * 4 + r]);
+                }
+            lrun[qt] = lrun[qt] * alpha + ps;
+            const bf16x8 pH = as_bf16x8(make_uint4(ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16), ph[6] | (ph[7] << 16)));
+            const bf16x8 pL = as_bf16x8(make_uint4(plo[0] | (plo[1] << 16), plo[2] | (plo[3] << 16), plo[4] | (plo[5] << 16), plo[6] | (plo[7] << 16)));
+#pragma unroll
+            for (int tp = 0; tp < 4; ++tp) {
+                // dims tile 2tp: tokens from the low halves of the two pages' loads; tile 2tp+1: high halves
+                const bf16x8 va = as_bf16x8(make_uint4(v0[tp].x, v0[tp].y, v1[tp].x, v1[tp].y));
+                const bf16x8 vb = as_bf16x8(make_uint4(v0[tp].z, v0[tp].w, v1[tp].z, v1[tp].w));
+                f32x4 oa = oacc[2 * tp][qt], ob = oacc[2 * tp + 1][qt];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { oa[r] *= alpha; ob[r] *= alpha; }
+                oa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pH, oa, 0, 0, 0);
+                oa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pL, oa, 0, 0, 0);
+                ob = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pH, ob, 0, 0, 0);
+                ob = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pL, ob, 0, 0, 0);
+                oacc[2 * tp][qt] = oa;
+                oacc[2 * tp + 1][qt] = ob;
+            }
+        }
+    }
+
+    // ---- merge the 4 waves pairwise through LDS, in the accumulators' own register layout
+    // (wave 1 -> 0 and 3 -> 2, then 2 -> 0); wave 0 writes the block's partial result.
+    float *slotO = lds;                                 // [2 slots][64 regs][64 lanes]
+    float *slotM = lds + 2 * 64 * 64;                   // [2 slots][2 qt][64 lanes] (max), then the same for sums
+    float *slotL = slotM + 2 * 2 * 64;
+    auto put = [&](int sl) {
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            slotM[(sl * 2 + qt) * 64 + lane] = mrun[qt];
+            slotL[(sl * 2 + qt) * 64 + lane] = lrun[qt];
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) slotO[(sl * 64 + (t * 2 + qt) * 4 + r) * 64 + lane] = oacc[t][qt][r];
+        }
+    };
+    auto take = [&](int sl) {
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            const float mo = slotM[(sl * 2 + qt) * 64 + lane], lo_ = slotL[(sl * 2 + qt) * 64 + lane];
+            const float mnew = fmaxf(mrun[qt], mo);
+            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+            const float sa = exp2f(mrun[qt] - muse), sb = exp2f(mo - muse);
+            mrun[qt] = mnew;
+            lrun[qt] = lrun[qt] * sa + lo_ * sb;
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    oacc[t][qt][r] = oacc[t][qt][r] * sa + slotO[(sl * 64 + (t * 2 + qt) * 4 + r) * 64 + lane] * sb;
+        }
+    };
+    if (wave & 1) put(wave >> 1);
+    __syncthreads();
+    if (!(wave & 1)) take(wave >> 1);
+    __syncthreads();
+    if (wave == 2) put(0);
+    __syncthreads();
+    if (wave == 0) {
+        take(0);
+        const size_t base = ((size_t)item * g.Hkv + kvh) * 32;
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            float l = lrun[qt];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const int q = qt * 16 + qi;
+            if (grp == 0) att_ml[base + q] = make_float2(mrun[qt], l);
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                *(float4 *)(att_o + (base + q) * 128 + t * 16 + 4 * grp) =
+                    make_float4(oacc[t][qt][0], oacc[t][qt][1], oacc[t][qt][2], oacc[t][qt][3]);
+        }
+    }
+}
+
+// cross-chunk merge + normalisation; writes the attention output as hi/lo fragments for the O projection.
+// grid (merge groups, Hkv), 256 threads: thread owns (row q = t/8, 16 dims).
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float *att_o, const float2 *att_ml, DevPlan p, int Hq, int Hkv,
+                                                         uint16_t *o_pack, int m_tiles) {
+    const int grpi = blockIdx.x, kvh = blockIdx.y;
+    const int b = p.mg_req[grpi], rg = p.mg_rg[grpi], item0 = p.mg_item0[grpi], cnt = p.mg_count[grpi];
+    const int n = p.req_n[b], row0 = p.req_row0[b], G = Hq / Hkv;
+    const int q = threadIdx.x >> 3, d0 = (threadIdx.x & 7) * 16;
+    const int R = rg * 32 + q;
+    if (R >= G * n) return;
+    const int hg = R / n, node = R - hg * n;
+    float mg = -INFINITY;
+    for (int c = 0; c < cnt; ++c) mg = fmaxf(mg, att_ml[((size_t)(item0 + c) * Hkv + kvh) * 32 + q].x);
+    float acc[16], l = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+    for (int c = 0; c < cnt; ++c) {
+        const size_t base = ((size_t)(item0 + c) * Hkv + kvh) * 32 + q;
+        const float2 ml = att_ml[base];
+        const float sc = exp2f(ml.x - mg);
+        l += sc * ml.y;
+        const float *o = att_o + base * 128 + d0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] += sc * o[e];
+    }
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] *= inv;
+    const int m = row0 + node, k0 = (kvh * G + hg) * 128 + d0;
+    store_split8(o_pack, m, k0, m_tiles, acc);
+    store_split8(o_pack, m, k0 + 8, m_tiles, acc + 8);
+}
+
+// ---------------------------------------------------------------------------
+// host orchestration of one forward pass
+// ---------------------------------------------------------------------------
+struct GemmPlan {
+    int NT, S;
+};
+
+static GemmPlan plan_gemm(int n_tiles, int k_steps, int rows, size_t part_elems, int N, bool allow_split) {
+    GemmPlan gp;
+    const int n_stages = k_steps / 2;
+    int ctas2 = (n_tiles + 7) / 8;
+    gp.NT = (ctas2 >= 192 && n_tiles % 2 == 0) ? 2 : 1;
+    const int ctas = (n_tiles + 4 * gp.NT - 1) / (4 * gp.NT);
+    int S = 1;
+    if (allow_split) {
+        S = (256 + ctas - 1) / ctas;
+        S = std::min(S, 8);
+        S = std::min(S, std::max(1, n_stages / 8));
+        while (S > 1 && (size_t)S * rows * N > part_elems) --S;
+    }
+    gp.S = std::max(S, 1);
+    return gp;
+}
+
+template <int EPI>
+static void launch_gemm(const GemmArgs &ga, int NT, int S, int m_tiles, hipStream_t st) {
+    const int mblocks = (m_tiles + 3) / 4;
+    const int MT = m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1);
+    dim3 grid((ga.n_tiles + 4 * NT - 1) / (4 * NT), S, mblocks);
+    const size_t lds = (size_t)2 * 2 * MT * 2 * 64 * 16;
+#define SEV_LAUNCH(MT_, NT_)                                                                                          \
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, 4>), grid, dim3(256), lds, st, ga)
+    if constexpr (EPI == EPI_SWIGLU) {
+        if (MT == 4) SEV_LAUNCH(4, 2); else if (MT == 2) SEV_LAUNCH(2, 2); else SEV_LAUNCH(1, 2);
+    } else if (NT == 2) {
+        if (MT == 4) SEV_LAUNCH(4, 2); else if (MT == 2) SEV_LAUNCH(2, 2); else SEV_LAUNCH(1, 2);
+    } else {
+        if (MT == 4) SEV_LAUNCH(4, 1); else if (MT == 2) SEV_LAUNCH(2, 1); else SEV_LAUNCH(1, 1);
+    }
+#undef SEV_LAUNCH
+}
+
+void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, float *logits_out,
+                  hipStream_t st) {
+    (void)B;
+    const sev_model_desc &d = m->d;
+    KvGeom g = sev_kv_geom(kv);
+    const int m_tiles_real = (rows + 31) / 32;
+    const int m_tiles = (m_tiles_real + 3) / 4 * 4;
+    auto Wp = [&](size_t off) { return (const uint4 *)(m->arena + off); };
+    auto Gp = [&](size_t off) { return (const float *)(m->arena + off); };
+    uint16_t *xa = (uint16_t *)kv->xa, *qp = (uint16_t *)kv->q_buf, *op = (uint16_t *)kv->o_buf, *act = (uint16_t *)kv->act;
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)d.head_dim);
+
+    {
+        Prof p(kv, st, PROF_OTHER);
+        hipLaunchKernelGGL(embed_norm_kernel, dim3(rows), dim3(256), 0, st, (const uint16_t *)(m->arena + m->off_embed),
+                           kv->plan.row_tok, Gp(m->layers[0].g_attn), kv->h, xa, d.d_model, m_tiles, d.rms_eps);
+    }
+    const GemmPlan pq = plan_gemm(m->n_qkv / 32, d.d_model / 16, rows, kv->part_elems, m->n_qkv, true);
+    const GemmPlan po = plan_gemm(d.d_model / 32, m->q_dim / 16, rows, kv->part_elems, d.d_model, true);
+    const GemmPlan pd = plan_gemm(d.d_model / 32, d.d_ffn / 16, rows, kv->part_elems, d.d_model, true);
+    for (int l = 0; l < d.n_layers; ++l) {
+        const LayerOffsets &lo = m->layers[l];
+        GemmArgs ga;
+        memset(&ga, 0, sizeof(ga));
+        ga.m_tiles_total = m_tiles;
+        ga.M = rows;
+        {   // QKV projection -> split-K partials
+            Prof p(kv, st, PROF_GEMM_QKV);
+            ga.W = Wp(lo.wqkv); ga.X = (const uint4 *)xa; ga.n_tiles = m->n_qkv / 32; ga.k_steps = d.d_model / 16;
+            ga.N = m->n_qkv; ga.part = kv->part;
+            launch_gemm<EPI_PARTIAL>(ga, pq.NT, pq.S, m_tiles_real, st);
+        }
+        {
+            Prof p(kv, st, PROF_OTHER);
+            hipLaunchKernelGGL(rope_kv_bf16_kernel, dim3(rows, d.n_q_heads + d.n_kv_heads), dim3(64), 0, st, kv->part, pq.S,
+                               rows, m->n_qkv, kv->plan, g, kv->page_table, kv->max_pages_per_req, l, d.n_q_heads, qp);
+        }
+        {
+            Prof p(kv, st, PROF_ATTN);
+            const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 2 * 64) * 4;
+            hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan, g,
+                               kv->page_table, kv->max_pages_per_req, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e);
+            hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
+                               kv->plan, d.n_q_heads, d.n_kv_heads, op, m_tiles);
+        }
+        {   // output projection -> partials; residual + FFN norm
+            Prof p(kv, st, PROF_GEMM_O);
+            ga.W = Wp(lo.wo); ga.X = (const uint4 *)op; ga.n_tiles = d.d_model / 32; ga.k_steps = m->q_dim / 16;
+            ga.N = d.d_model; ga.part = kv->part;
+            launch_gemm<EPI_PARTIAL>(ga, po.NT, po.S, m_tiles_real, st);
+        }
+        {
+            Prof p(kv, st, PROF_OTHER);
+            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(256), 0, st, kv->h, kv->part, po.S, rows, Gp(lo.g_ffn), xa,
+                               d.d_model, m_tiles, d.rms_eps);
+        }
+        {   // gate/up projection with fused SwiGLU
+            Prof p(kv, st, PROF_GEMM_GU);
+            ga.W = Wp(lo.wgu); ga.X = (const uint4 *)xa; ga.n_tiles = 2 * d.d_ffn / 32; ga.k_steps = d.d_model / 16;
+            ga.N = 2 * d.d_ffn; ga.act = act;
+            launch_gemm<EPI_SWIGLU>(ga, 2, 1, m_tiles_real, st);
+        }
+        {   // down projection -> partials; residual + next norm
+            Prof p(kv, st, PROF_GEMM_DOWN);
+            ga.W = Wp(lo.wd); ga.X = (const uint4 *)act; ga.n_tiles = d.d_model / 32; ga.k_steps = d.d_ffn / 16;
+            ga.N = d.d_model; ga.part = kv->part;
+            launch_gemm<EPI_PARTIAL>(ga, pd.NT, pd.S, m_tiles_real, st);
+        }
+        {
+            Prof p(kv, st, PROF_OTHER);
+            const float *gn = (l + 1 < d.n_layers) ? Gp(m->layers[l + 1].g_attn) : Gp(m->off_gfinal);
+            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(256), 0, st, kv->h, kv->part, pd.S, rows, gn, xa, d.d_model,
+                               m_tiles, d.rms_eps);
+        }
+    }
+    {   // LM head with fused arg-max
+        Prof p(kv, st, PROF_GEMM_LM);
+        GemmArgs ga;
+        memset(&ga, 0, sizeof(ga));
+        ga.m_tiles_total = m_tiles; ga.M = rows;
+        ga.W = Wp(m->off_lm); ga.X = (const uint4 *)xa; ga.n_tiles = d.vocab / 32; ga.k_steps = d.d_model / 16; ga.N = d.vocab;
+        ga.lm_val = kv->lm_val; ga.lm_idx = kv->lm_idx; ga.lm_stride = m_tiles * 32; ga.logits = logits_out;
+        const int NT = (ga.n_tiles % 2 == 0) ? 2 : 1;
+        launch_gemm<EPI_ARGMAX>(ga, NT, 1, m_tiles_real, st);
+        const int n_part = ((ga.n_tiles + 4 * NT - 1) / (4 * NT)) * 4;
+        hipLaunchKernelGGL(lm_reduce_kernel, dim3(rows), dim3(256), 0, st, kv->lm_val, kv->lm_idx, n_part, ga.lm_stride,
+                           kv->row_argmax);
+    }
+}

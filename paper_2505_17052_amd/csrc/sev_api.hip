@@ -262,8 +262,8 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     const size_t o_act = take(rows_pad * d.d_ffn * 4);
     const size_t o_ao = take(bf ? (size_t)kv->max_items * d.n_kv_heads * 32 * d.head_dim * 4 : 4);
     const size_t o_ml = take(bf ? (size_t)kv->max_items * d.n_kv_heads * 32 * 8 : 4);
-    const size_t o_lv = take(bf ? (size_t)(d.vocab / 32) * rows_pad * 4 : 4);
-    const size_t o_li = take(bf ? (size_t)(d.vocab / 32) * rows_pad * 4 : 4);
+    const size_t o_lv = take(bf ? (size_t)(d.vocab / 32 + 4) * rows_pad * 4 : 4);
+    const size_t o_li = take(bf ? (size_t)(d.vocab / 32 + 4) * rows_pad * 4 : 4);
     const size_t o_am = take(rows_pad * 4);
     const size_t o_lg = take(bf ? 4 : rows_pad * (size_t)d.vocab * 4);
     kv->ws_bytes = off;

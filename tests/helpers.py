@@ -32,3 +32,56 @@ def decision_gap_ok(res, gap_min: float) -> bool:
 
 def announce(msg: str):
     print(f"[case] {msg}", flush=True)
+
+
+def oracle_caches_synthetic(om, shape, seed, prefix_lens, last_tokens, extra=80):
+    """Oracle-side twin of harness.Batch.fill_synthetic: drawn K/V for positions 0..P-2, then a real
+    forward over the last prefix token (position P-1), which also yields next_tok."""
+    caches = []
+    for b, P in enumerate(prefix_lens):
+        c = vo.Cache(om, P + extra)
+        if P > 1:
+            for l in range(shape.n_layers):
+                K, V = synth.synthetic_kv(shape, seed, b, l, P - 1)
+                if K.dtype == np.uint16:
+                    K, V = synth.bf16_bits_to_f32(K), synth.bf16_bits_to_f32(V)
+                c.K[l][:P - 1] = K
+                c.V[l][:P - 1] = V
+        c.length = P - 1
+        caches.append(c)
+    vo.extend(om, caches, [np.array([int(t)]) for t in last_tokens])
+    return caches
+
+
+def tree_tokens(om, caches, parents_list, reqs, vocab, p_keep=0.7):
+    """Tokens for draft trees, level by level: at every node one designated child receives the target's
+    own arg-max with probability p_keep (else a random id); its siblings get distinct random ids.
+    Uses one oracle forward per level (the tree so far) to learn the arg-max at the new parents."""
+    R = len(caches)
+    toks = [np.zeros(len(p), dtype=np.int64) for p in parents_list]
+    deps = [vo.depths(np.asarray(p)) for p in parents_list]
+    max_d = max(int(d.max()) for d in deps)
+    amax = [None] * R
+    for lvl in range(max_d + 1):
+        for r in range(R):
+            par, req = np.asarray(parents_list[r]), reqs[r]
+            nodes = [i for i in range(len(par)) if deps[r][i] == lvl]
+            by_parent = {}
+            for i in nodes:
+                by_parent.setdefault(int(par[i]), []).append(i)
+            for pnode, kids in by_parent.items():
+                want = caches[r].next_tok if pnode < 0 else int(amax[r][pnode])
+                used = set()
+                for j, i in enumerate(kids):
+                    if j == 0 and req.corrupt_draw[i % len(req.corrupt_draw)] < p_keep:
+                        t = want
+                    else:
+                        t = int(req.random_tokens[i % len(req.random_tokens)])
+                        while t in used or t == want:
+                            t = (t + 1) % vocab
+                    used.add(t)
+                    toks[r][i] = t
+        # arg-max at all nodes placed so far (deeper nodes still hold 0: they do not influence shallower ones)
+        lg, _, _ = vo.forward_blocks(om, caches, toks, parents_list)
+        amax = [np.argmax(l, axis=-1) for l in lg]
+    return toks
