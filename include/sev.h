@@ -116,9 +116,13 @@ int sev_kv_destroy(sev_kv *kv);
 int sev_kv_set_pages(sev_kv *kv, int slot, const int32_t *page_ids /*[host]*/, int n_pages,
                      void *stream);
 
-/* Sets a slot's committed length and the target's prediction for the next
- * position (used after importing cache contents).  Clears any pending block. */
-int sev_kv_set_state(sev_kv *kv, int slot, int32_t seq_len, int32_t next_tok, void *stream);
+/* Sets the committed length and the target's prediction for the next position of B
+ * slots at once (used after importing cache contents, and to rewind a slot to an
+ * earlier committed state).  slots, seq_lens, next_toks are [host] int32[B]
+ * (slots NULL = 0..B-1; next_tok -1 = unknown).  Clears any pending block.  One
+ * kernel launch; the arrays are copied at call time. */
+int sev_kv_set_state(sev_kv *kv, const int32_t *slots /*[host]*/, const int32_t *seq_lens /*[host]*/,
+                     const int32_t *next_toks /*[host]*/, int B, void *stream);
 
 /* Copies n_tokens positions starting at logical position `start` of one layer
  * of a slot between the paged cache and a plain [n_tokens][n_kv_heads][head_dim]
@@ -202,11 +206,13 @@ int sev_kv_rollback(sev_kv *kv, const int32_t *slots /*[host]*/, int B, void *st
 
 const char *sev_last_error(void);
 
-/* Average device time in milliseconds of kernel class `which` over the calls
- * since the last reset, measured with HIP events on the launch stream when
- * profiling is enabled with sev_profile_enable(kv, 1) (adds event records around
- * each launch; off by default).  See sev_profile_name for the classes. */
-int sev_profile_enable(sev_kv *kv, int on);
+/* Per-kernel-class device time, measured with HIP events recorded on the launch
+ * stream around every launch of the selected classes.  sev_profile_enable resets
+ * the totals and selects classes by bit mask (bit i = class i, 0 = off; off by
+ * default).  sev_profile_read waits for the recorded events and returns the total
+ * milliseconds and the number of timed spans of class `which` since the reset.
+ * See sev_profile_name for the classes. */
+int sev_profile_enable(sev_kv *kv, unsigned class_mask);
 int sev_profile_read(sev_kv *kv, int which, double *total_ms, int64_t *launches);
 const char *sev_profile_name(int which);   /* NULL beyond the last class */
 

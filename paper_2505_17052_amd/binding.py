@@ -55,7 +55,7 @@ def lib():
         "sev_kv_create": (i32, [vp, i32, i32, i64, i32, vp, sz, C.POINTER(vp)]),
         "sev_kv_destroy": (i32, [vp]),
         "sev_kv_set_pages": (i32, [vp, i32, vp, i32, vp]),
-        "sev_kv_set_state": (i32, [vp, i32, C.c_int32, C.c_int32, vp]),
+        "sev_kv_set_state": (i32, [vp, vp, vp, vp, i32, vp]),
         "sev_kv_copy_tokens": (i32, [vp, i32, i32, i32, i32, vp, vp, i32, vp]),
         "sev_kv_get_state": (i32, [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint32), vp]),
         "sev_verify": (i32, [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]),
@@ -63,7 +63,7 @@ def lib():
         "sev_kv_commit": (i32, [vp, vp, i32, vp]),
         "sev_kv_rollback": (i32, [vp, vp, i32, vp]),
         "sev_last_error": (C.c_char_p, []),
-        "sev_profile_enable": (i32, [vp, i32]),
+        "sev_profile_enable": (i32, [vp, C.c_uint]),
         "sev_profile_read": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "sev_profile_name": (C.c_char_p, [i32]),
     }
@@ -154,8 +154,12 @@ class KVCache:
         a = _host_i32(page_ids)
         _check(lib().sev_kv_set_pages(self.handle, slot, _hp(a), len(a), _stream_ptr()), "sev_kv_set_pages")
 
-    def set_state(self, slot: int, seq_len: int, next_tok: int):
-        _check(lib().sev_kv_set_state(self.handle, slot, seq_len, next_tok, _stream_ptr()), "sev_kv_set_state")
+    def set_state(self, slot, seq_len, next_tok):
+        """Scalars (one slot) or equal-length sequences (several slots; slot may be None for 0..B-1)."""
+        if np.isscalar(seq_len):
+            slot, seq_len, next_tok = [slot], [seq_len], [next_tok]
+        sl, ln, nt = _host_i32(slot), _host_i32(seq_len), _host_i32(next_tok)
+        _check(lib().sev_kv_set_state(self.handle, _hp(sl), _hp(ln), _hp(nt), len(ln), _stream_ptr()), "sev_kv_set_state")
 
     def get_state(self, slot: int):
         a, b, f = C.c_int32(), C.c_int32(), C.c_uint32()
@@ -167,8 +171,15 @@ class KVCache:
         _check(lib().sev_kv_copy_tokens(self.handle, slot, layer, start, n_tokens, _dp(k), _dp(v), int(to_cache),
                                         _stream_ptr()), "sev_kv_copy_tokens")
 
-    def profile_enable(self, on: bool):
-        _check(lib().sev_profile_enable(self.handle, int(on)), "sev_profile_enable")
+    def profile_enable(self, class_mask: int):
+        _check(lib().sev_profile_enable(self.handle, int(class_mask)), "sev_profile_enable")
+
+    def profile_classes(self):
+        out, i = [], 0
+        while lib().sev_profile_name(i) is not None:
+            out.append(lib().sev_profile_name(i).decode())
+            i += 1
+        return out
 
     def profile_read(self):
         out, i = {}, 0

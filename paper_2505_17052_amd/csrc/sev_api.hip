@@ -359,20 +359,35 @@ extern "C" int sev_kv_set_pages(sev_kv *kv, int slot, const int32_t *page_ids, i
     return SEV_OK;
 }
 
-__global__ void set_state_kernel(int32_t *seq_len, int32_t *next_tok, int32_t *pend_n, int slot, int len, int nt) {
-    seq_len[slot] = len;
-    next_tok[slot] = nt;
-    pend_n[slot] = 0;
+struct StateArgs {
+    int32_t slot[SEV_MAX_BATCH], len[SEV_MAX_BATCH], nt[SEV_MAX_BATCH];
+};
+
+__global__ void set_state_kernel(StateArgs a, int B, int32_t *seq_len, int32_t *next_tok, int32_t *pend_n) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    seq_len[a.slot[b]] = a.len[b];
+    next_tok[a.slot[b]] = a.nt[b];
+    pend_n[a.slot[b]] = 0;
 }
 
-extern "C" int sev_kv_set_state(sev_kv *kv, int slot, int32_t seq_len, int32_t next_tok, void *stream) {
-    if (!kv) return sev_fail(SEV_EINVAL, "null cache");
-    if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "slot %d out of range", slot);
-    if (seq_len < 0 || (int64_t)seq_len > (int64_t)kv->host_pages[slot] * SEV_PAGE)
-        return sev_fail(SEV_ENOSPACE, "length %d exceeds the %d pages of slot %d", seq_len, kv->host_pages[slot], slot);
-    if (next_tok < -1 || next_tok >= kv->model->d.vocab) return sev_fail(SEV_EINVAL, "next_tok out of range");
-    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(1), 0, (hipStream_t)stream, kv->seq_len, kv->next_tok, kv->pend_n,
-                       slot, seq_len, next_tok);
+extern "C" int sev_kv_set_state(sev_kv *kv, const int32_t *slots, const int32_t *seq_lens, const int32_t *next_toks,
+                                int B, void *stream) {
+    if (!kv || !seq_lens || !next_toks) return sev_fail(SEV_EINVAL, "null argument");
+    if (B < 1 || B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", B, SEV_MAX_BATCH);
+    StateArgs a;
+    for (int b = 0; b < B; ++b) {
+        const int slot = slots ? slots[b] : b;
+        if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "slot %d out of range", slot);
+        if (seq_lens[b] < 0 || (int64_t)seq_lens[b] > (int64_t)kv->host_pages[slot] * SEV_PAGE)
+            return sev_fail(SEV_ENOSPACE, "length %d exceeds the %d pages of slot %d", seq_lens[b], kv->host_pages[slot], slot);
+        if (next_toks[b] < -1 || next_toks[b] >= kv->model->d.vocab) return sev_fail(SEV_EINVAL, "next_tok out of range");
+        a.slot[b] = slot;
+        a.len[b] = seq_lens[b];
+        a.nt[b] = next_toks[b];
+    }
+    hipLaunchKernelGGL(set_state_kernel, dim3((B + 63) / 64), dim3(64), 0, (hipStream_t)stream, a, B, kv->seq_len,
+                       kv->next_tok, kv->pend_n);
     SEV_HIP(hipGetLastError());
     return SEV_OK;
 }
@@ -412,7 +427,7 @@ extern "C" int sev_kv_copy_tokens(sev_kv *kv, int slot, int layer, int start, in
 // profiling spans
 // ---------------------------------------------------------------------------
 Prof::Prof(sev_kv *kv_, hipStream_t st_, int cls_) : kv(kv_), st(st_), cls(cls_), a(nullptr), b(nullptr), on(false) {
-    if (!kv->prof_on) return;
+    if (!((kv->prof_on >> cls_) & 1)) return;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
     on = true;
     hipEventRecord(a, st);
@@ -437,10 +452,10 @@ static void prof_collect(sev_kv *kv) {
     kv->spans.clear();
 }
 
-extern "C" int sev_profile_enable(sev_kv *kv, int on) {
+extern "C" int sev_profile_enable(sev_kv *kv, unsigned class_mask) {
     if (!kv) return sev_fail(SEV_EINVAL, "null cache");
     prof_collect(kv);
-    kv->prof_on = on ? 1 : 0;
+    kv->prof_on = (int)(class_mask & ((1u << PROF_N) - 1));
     memset(kv->prof_ms, 0, sizeof(kv->prof_ms));
     memset(kv->prof_n, 0, sizeof(kv->prof_n));
     return SEV_OK;
