@@ -18,6 +18,7 @@ KvGeom sev_kv_geom(const sev_kv *kv);
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native 16-byte vector (keeps staging arrays in registers)
 
 // ---------------------------------------------------------------------------
 // small helpers
@@ -46,12 +47,16 @@ __device__ __forceinline__ void store_split8(uint16_t *xp, int m, int k0, int m_
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__device__ __forceinline__ float block_sum_256(float v, float *red) {
+template <int THREADS>
+__device__ __forceinline__ float block_sum(float v, float *red) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    const float s = red[0] + red[1] + red[2] + red[3];
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < THREADS / 64; ++w) s += red[w];
     __syncthreads();
     return s;
 }
@@ -59,26 +64,42 @@ __device__ __forceinline__ float block_sum_256(float v, float *red) {
 // ---------------------------------------------------------------------------
 // weight re-tiling: canonical [rows][K] bf16 -> [tile][K/16][lane 64][8], where lane
 // (n % 32) + 32*((k/8)%2) holds W[n][k..k+7]: exactly the A operand of a 32x32x16 MFMA.
-// Source tile t lands at destination tile t*tile_mul + tile_add (gate/up interleave, fused QKV).
+//
+// mode 0: source tile t lands at destination tile t + tile_add (plain, or a row range of a fused matrix).
+// mode 1 / 2 (gate / up of the SwiGLU pair): destination tile t holds feed-forward columns
+// [16t, 16t+16) of BOTH matrices, 4-row groups alternating so that an MFMA output lane owns the
+// gate and the up value of the same 4 columns: tile row n = 8j + 4h + r (j = 0..3, h = 0..1, r = 0..3)
+// is the gate (j even) or up (j odd) row 16t + 8(j/2) + 4h + r.
 // ---------------------------------------------------------------------------
-__global__ void pack_bf16_kernel(uint4 *dst, const uint16_t *src, int K, int64_t n_chunks, int tile_mul, int tile_add) {
+__global__ void pack_bf16_kernel(uint4 *dst, const uint16_t *src, int K, int64_t n_chunks, int mode, int tile_add) {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= n_chunks) return;
     const int ksteps = K >> 4;
     const int lane = (int)(c & 63);
     const int64_t tk = c >> 6;
     const int kt = (int)(tk % ksteps);
-    const int64_t t = tk / ksteps;
-    const int64_t n = t * 32 + (lane & 31);
+    const int64_t t = tk / ksteps;                   // destination tile
+    const int n = lane & 31;
     const int k = kt * 16 + 8 * (lane >> 5);
-    const uint4 v = *(const uint4 *)(src + n * K + k);
-    dst[((t * tile_mul + tile_add) * ksteps + kt) * 64 + lane] = v;
+    int64_t row;
+    if (mode == 0) {
+        row = (t - tile_add) * 32 + n;
+    } else {
+        const int j = n >> 3;
+        if ((j & 1) != mode - 1) return;             // this launch fills only its own 4-row groups
+        row = t * 16 + 8 * (j >> 1) + (n & 7);
+    }
+    dst[(t * ksteps + kt) * 64 + lane] = *(const uint4 *)(src + row * K + k);
 }
 
-void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int tile_mul, int tile_add, hipStream_t st) {
-    const int64_t n_chunks = (int64_t)(n_rows / 32) * (K / 16) * 64;
-    hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, (uint4 *)dst, src,
-                       K, n_chunks, tile_mul, tile_add);
+// n_rows source rows.  mode 0: destination tiles tile_add .. tile_add + n_rows/32 - 1;
+// modes 1, 2: destination tiles 0 .. n_rows/16 - 1.
+void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int mode, int tile_add, hipStream_t st) {
+    const int64_t tiles = mode == 0 ? n_rows / 32 : n_rows / 16;
+    const int64_t n_chunks = tiles * (K / 16) * 64;
+    uint4 *d = (uint4 *)dst + (mode == 0 ? (int64_t)tile_add * (K / 16) * 64 : 0);
+    hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, d, src, K, n_chunks,
+                       mode, 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -105,7 +126,7 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, cons
         *(float4 *)(hr + c * 8) = make_float4(v[0], v[1], v[2], v[3]);
         *(float4 *)(hr + c * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
     }
-    ss = block_sum_256(ss, red);
+    ss = block_sum<256>(ss, red);
     const float r = 1.0f / sqrtf(ss / (float)d + eps);
     for (int c = threadIdx.x; c < d / 8; c += 256) {
         float v[8];
@@ -119,13 +140,13 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, cons
 // residual add of split-K partial sums + RMSNorm of the updated stream.  One block per row.
 //   h[m] += sum_s part[s][m]   (fixed order)        xa = split(rmsnorm(h[m]) * g)
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void resid_norm_kernel(float *h, const float *part, int S, int M, const float *g,
-                                                         uint16_t *xa, int d, int m_tiles, float eps) {
-    __shared__ float red[4];
+__global__ __launch_bounds__(1024) void resid_norm_kernel(float *h, const float *part, int S, int M, const float *g,
+                                                          uint16_t *xa, int d, int m_tiles, float eps) {
+    __shared__ float red[16];
     const int m = blockIdx.x;
     float *hr = h + (size_t)m * d;
     float ss = 0.f;
-    for (int c = threadIdx.x; c < d / 4; c += 256) {
+    for (int c = threadIdx.x; c < d / 4; c += 1024) {
         float4 a = *(float4 *)(hr + c * 4);
         for (int s = 0; s < S; ++s) {
             const float4 p = *(const float4 *)(part + ((size_t)s * M + m) * d + c * 4);
@@ -134,9 +155,9 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(float *h, const float *
         *(float4 *)(hr + c * 4) = a;
         ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
     }
-    ss = block_sum_256(ss, red);        // also orders the writes of h before the reads below
+    ss = block_sum<1024>(ss, red);      // also orders the writes of h before the reads below
     const float r = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = threadIdx.x; c < d / 8; c += 256) {
+    for (int c = threadIdx.x; c < d / 8; c += 1024) {
         float v[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[i] = hr[c * 8 + i] * r * g[c * 8 + i];
@@ -162,7 +183,7 @@ struct GemmArgs {
     const uint4 *X;          // xpack activations
     int n_tiles, k_steps, m_tiles_total, M, N;
     float *part;             // EPI_PARTIAL: [S][M][N]
-    uint16_t *act;           // EPI_SWIGLU: xpack with K = N/2
+    uint16_t *act;           // EPI_SWIGLU: xpack with K = N/2 (N counts gate and up rows)
     float *lm_val;           // EPI_ARGMAX: [gridDim.x*4][lm_stride]
     int32_t *lm_idx;
     int lm_stride;
@@ -171,7 +192,7 @@ struct GemmArgs {
 
 template <int MT, int NT, int EPI, int PF>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
-    extern __shared__ uint4 xs[];                       // [2 buffers][2 k-steps][MT][2 planes][64 lanes]
+    extern __shared__ u32x4 xs[];                       // [2 buffers][2 k-steps][MT][2 planes][64 lanes]
     constexpr int STAGE_U4 = 2 * MT * 2 * 64;           // uint4 per stage
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int tile0 = (blockIdx.x * 4 + wave) * NT;
@@ -190,74 +211,100 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
     // weight fragment pointers of this lane (clamped to a valid tile so idle waves load harmlessly)
-    const uint4 *wp[NT];
+    const u32x4 *wp[NT];
 #pragma unroll
     for (int a = 0; a < NT; ++a) {
         const int t = min(tile0 + a, g.n_tiles - 1);
-        wp[a] = g.W + ((size_t)t * g.k_steps) * 64 + lane;
+        wp[a] = (const u32x4 *)g.W + ((size_t)t * g.k_steps) * 64 + lane;
     }
-    uint4 wreg[PF][NT][2];
-    uint4 x0, x1, x2, x3;                               // activation staging (scalars: MT <= 4 are used)
-    x0 = x1 = x2 = x3 = make_uint4(0, 0, 0, 0);
-
-    auto load_w = [&](int u, int st) {
+    // Software pipeline.  Loads return in issue order, so a wait on one load drains every older one:
+    // to keep PF stages in flight, weights AND activations are fetched PF stages ahead into registers
+    // and consumed in the order they were issued.  At stage st (slot u = st % PF):
+    //   LDS buffer st&1 holds X(st);  wreg[u] holds W(st);  xreg[u] holds X(st+1).
+    // The loop body is PF stages of straight-line code (no branches), which lets the compiler's
+    // wait-count bookkeeping follow the loads across the back-edge.  The slice is padded to a multiple
+    // of PF stages: padded stages re-load the last stage (cached) and feed zero activations.
+    static_assert(PF % 2 == 0, "LDS buffer parity must follow the slot index");
+    u32x4 wreg[PF][NT][2];
+    u32x4 xreg[PF][MT];
+    const u32x4 *xsrc[MT];
 #pragma unroll
-        for (int a = 0; a < NT; ++a)
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = wp[a][(size_t)(2 * st + ks) * 64];
-    };
-    // the stage's activation fragments are MT*256 consecutive 16-byte units per k-step pair
-    auto x_src = [&](int st, int i) -> const uint4 * {
+    for (int i = 0; i < MT; ++i) {
         const int u = threadIdx.x + 256 * i;
         const int ksl = u / (MT * 128), within = u - ksl * (MT * 128);
-        return g.X + ((size_t)(2 * st + ksl) * g.m_tiles_total + mt0) * 128 + within;
-    };
-    auto load_x = [&](int st) {
-        x0 = *x_src(st, 0);
-        if constexpr (MT > 1) x1 = *x_src(st, 1);
-        if constexpr (MT > 2) { x2 = *x_src(st, 2); x3 = *x_src(st, 3); }
-    };
-    auto store_x = [&](int buf) {
-        uint4 *dst = xs + buf * STAGE_U4 + threadIdx.x;
-        dst[0] = x0;
-        if constexpr (MT > 1) dst[256] = x1;
-        if constexpr (MT > 2) { dst[512] = x2; dst[768] = x3; }
-    };
-
-    // Prologue: PF weight stages in flight, first activation stage in LDS.  Stage indices past the
-    // slice end are clamped (a redundant, cached re-load) so the pipeline body stays branch-free.
+        xsrc[i] = (const u32x4 *)g.X + ((size_t)ksl * g.m_tiles_total + mt0) * 128 + within;
+    }
+    const size_t x_stage = (size_t)2 * g.m_tiles_total * 128;      // 16-byte units per stage of all row tiles
     const int s_last = s_end - 1;
+    const int n_pad = (n + PF - 1) / PF * PF;
+
+    {
+        u32x4 x0[MT];
 #pragma unroll
-    for (int u = 0; u < PF; ++u) load_w(u, min(s_begin + u, s_last));
-    load_x(s_begin);
-    store_x(0);
+        for (int i = 0; i < MT; ++i) x0[i] = xsrc[i][(size_t)s_begin * x_stage];
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int sx = min(s_begin + u + 1, s_last), sw = min(s_begin + u, s_last);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+#pragma unroll
+            for (int a = 0; a < NT; ++a)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = wp[a][(size_t)(2 * sw + ks) * 64];
+        }
+#pragma unroll
+        for (int i = 0; i < MT; ++i) xs[threadIdx.x + 256 * i] = x0[i];
+    }
     __syncthreads();
 
-    for (int base = 0; base < n; base += PF) {
+    for (int base = 0; base < n_pad; base += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int st = base + u;
-            if (st < n) {                                  // block-uniform
-                load_x(min(s_begin + st + 1, s_last));
-                const uint4 *xb = xs + (u & 1) * STAGE_U4;
+            // all activation fragments of the stage are requested from LDS up front, so that only the
+            // first MFMA of the stage waits for an LDS round trip
+            const u32x4 *xb = xs + (u & 1) * STAGE_U4 + lane;
+            u32x4 xf[2][MT][2];
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
+            for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int b = 0; b < MT; ++b) {
-                        const bf16x8 xh = as_bf16x8(xb[((ks * MT + b) * 2 + 0) * 64 + lane]);
-                        const bf16x8 xl = as_bf16x8(xb[((ks * MT + b) * 2 + 1) * 64 + lane]);
+                for (int b = 0; b < MT; ++b)
 #pragma unroll
-                        for (int a = 0; a < NT; ++a) {
-                            const bf16x8 w = as_bf16x8(wreg[u][a][ks]);
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, xh, acc[a][b], 0, 0, 0);
-                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, xl, acc[a][b], 0, 0, 0);
-                        }
+                    for (int pl = 0; pl < 2; ++pl) xf[ks][b][pl] = xb[((ks * MT + b) * 2 + pl) * 64];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+                for (int b = 0; b < MT; ++b) {
+#pragma unroll
+                    for (int a = 0; a < NT; ++a) {
+                        const bf16x8 w = as_bf16x8(wreg[u][a][ks]);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][0]), acc[a][b], 0, 0, 0);
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][1]), acc[a][b], 0, 0, 0);
                     }
                 }
-                load_w(u, min(s_begin + st + PF, s_last));
-                store_x((u + 1) & 1);
-                __syncthreads();
             }
+            __builtin_amdgcn_sched_barrier(0);
+            // next stage's activations: registers -> the other LDS buffer (zeros once past the slice end)
+            const bool live = st + 1 < n;
+            u32x4 *xd = xs + ((u + 1) & 1) * STAGE_U4 + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                u32x4 v = xreg[u][i];
+                if (!live) v = (u32x4){0u, 0u, 0u, 0u};
+                xd[256 * i] = v;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // refill this slot: activations first, then weights (the order they will be waited on)
+            const int sx = min(s_begin + st + PF + 1, s_last), sw = min(s_begin + st + PF, s_last);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+#pragma unroll
+            for (int a = 0; a < NT; ++a)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = wp[a][(size_t)(2 * sw + ks) * 64];
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
         }
     }
 
@@ -281,23 +328,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             }
         }
     } else if constexpr (EPI == EPI_SWIGLU) {
-        // tile pair (2t, 2t+1) = (gate tile t, up tile t)
-        if (tile0 + 1 < g.n_tiles) {
-            const int tp = tile0 >> 1;
+        // each 32-row weight tile holds gate (register groups j = 0, 2) and up (j = 1, 3) of 16 columns
+#pragma unroll
+        for (int a = 0; a < NT; ++a) {
+            if (tile0 + a >= g.n_tiles) continue;
 #pragma unroll
             for (int b = 0; b < MT; ++b) {
                 const int m = (mt0 + b) * 32 + mrow;
                 if (m >= g.M) continue;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int jj = 0; jj < 2; ++jj) {
                     uint32_t hi[4], lo[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const float gt = acc[0][b][4 * j + r], up = acc[NT - 1][b][4 * j + r];
+                        const float gt = acc[a][b][8 * jj + r], up = acc[a][b][8 * jj + 4 + r];
                         const float v = gt / (1.0f + __expf(-gt)) * up;
                         split_bf16(v, hi[r], lo[r]);
                     }
-                    const int f0 = tp * 32 + 8 * j + nsub;
+                    const int f0 = (tile0 + a) * 16 + 8 * jj + nsub;
                     *(uint2 *)(g.act + xpack_index(m, f0, 0, g.m_tiles_total)) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
                     *(uint2 *)(g.act + xpack_index(m, f0, 1, g.m_tiles_total)) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
                 }
@@ -651,6 +699,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *att_o, con
 // ---------------------------------------------------------------------------
 // host orchestration of one forward pass
 // ---------------------------------------------------------------------------
+#define GU_NT 1   // column tiles per wave in the gate/up GEMM
+
 struct GemmPlan {
     int NT, S;
 };
@@ -680,9 +730,7 @@ static void launch_gemm(const GemmArgs &ga, int NT, int S, int m_tiles, hipStrea
     const size_t lds = (size_t)2 * 2 * MT * 2 * 64 * 16;
 #define SEV_LAUNCH(MT_, NT_)                                                                                          \
     hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, 4>), grid, dim3(256), lds, st, ga)
-    if constexpr (EPI == EPI_SWIGLU) {
-        if (MT == 4) SEV_LAUNCH(4, 2); else if (MT == 2) SEV_LAUNCH(2, 2); else SEV_LAUNCH(1, 2);
-    } else if (NT == 2) {
+    if (NT == 2) {
         if (MT == 4) SEV_LAUNCH(4, 2); else if (MT == 2) SEV_LAUNCH(2, 2); else SEV_LAUNCH(1, 2);
     } else {
         if (MT == 4) SEV_LAUNCH(4, 1); else if (MT == 2) SEV_LAUNCH(2, 1); else SEV_LAUNCH(1, 1);
@@ -743,14 +791,14 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         }
         {
             Prof p(kv, st, PROF_OTHER);
-            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(256), 0, st, kv->h, kv->part, po.S, rows, Gp(lo.g_ffn), xa,
+            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(1024), 0, st, kv->h, kv->part, po.S, rows, Gp(lo.g_ffn), xa,
                                d.d_model, m_tiles, d.rms_eps);
         }
         {   // gate/up projection with fused SwiGLU
             Prof p(kv, st, PROF_GEMM_GU);
-            ga.W = Wp(lo.wgu); ga.X = (const uint4 *)xa; ga.n_tiles = 2 * d.d_ffn / 32; ga.k_steps = d.d_model / 16;
+            ga.W = Wp(lo.wgu); ga.X = (const uint4 *)xa; ga.n_tiles = d.d_ffn / 16; ga.k_steps = d.d_model / 16;
             ga.N = 2 * d.d_ffn; ga.act = act;
-            launch_gemm<EPI_SWIGLU>(ga, 2, 1, m_tiles_real, st);
+            launch_gemm<EPI_SWIGLU>(ga, GU_NT, 1, m_tiles_real, st);
         }
         {   // down projection -> partials; residual + next norm
             Prof p(kv, st, PROF_GEMM_DOWN);
@@ -761,7 +809,7 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         {
             Prof p(kv, st, PROF_OTHER);
             const float *gn = (l + 1 < d.n_layers) ? Gp(m->layers[l + 1].g_attn) : Gp(m->off_gfinal);
-            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(256), 0, st, kv->h, kv->part, pd.S, rows, gn, xa, d.d_model,
+            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(1024), 0, st, kv->h, kv->part, pd.S, rows, gn, xa, d.d_model,
                                m_tiles, d.rms_eps);
         }
     }

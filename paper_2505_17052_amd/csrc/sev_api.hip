@@ -142,7 +142,7 @@ extern "C" int sev_model_load_tensor(sev_model *m, int kind, int layer, const vo
     }
     // destination matrix (possibly a row range of a fused matrix): rows, K, row offset
     size_t off;
-    int rows, K, row0 = 0, tile_mul = 1, tile_add = 0;
+    int rows, K, row0 = 0, mode = 0;
     switch (kind) {
     case SEV_W_EMBED: off = m->off_embed; rows = d.vocab; K = d.d_model; break;
     case SEV_W_LM_HEAD: off = m->off_lm; rows = d.vocab; K = d.d_model; break;
@@ -150,9 +150,9 @@ extern "C" int sev_model_load_tensor(sev_model *m, int kind, int layer, const vo
     case SEV_W_WK: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim; break;
     case SEV_W_WV: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim + m->kv_dim; break;
     case SEV_W_WO: off = lo->wo; rows = d.d_model; K = m->q_dim; break;
-    // gate and up are interleaved by 32-row tiles in the bf16 layout (tile 2t = gate tile t, 2t+1 = up tile t)
-    case SEV_W_WG: off = lo->wgu; rows = d.d_ffn; K = d.d_model; tile_mul = 2; break;
-    case SEV_W_WU: off = lo->wgu; rows = d.d_ffn; K = d.d_model; tile_mul = 2; tile_add = 1; row0 = d.d_ffn; break;
+    // gate and up rows are interleaved in 4-row groups inside each 32-row tile of the bf16 layout
+    case SEV_W_WG: off = lo->wgu; rows = d.d_ffn; K = d.d_model; mode = 1; break;
+    case SEV_W_WU: off = lo->wgu; rows = d.d_ffn; K = d.d_model; mode = 2; row0 = d.d_ffn; break;
     case SEV_W_WD: off = lo->wd; rows = d.d_model; K = d.d_ffn; break;
     default: return sev_fail(SEV_EINVAL, "unknown tensor kind %d", kind);
     }
@@ -164,8 +164,7 @@ extern "C" int sev_model_load_tensor(sev_model *m, int kind, int layer, const vo
         // bf16 matrices are re-tiled into 32x16 MFMA operand fragments; a row offset inside a fused
         // matrix is a tile offset (all offsets are multiples of 32 by construction of the shapes)
         if (rows % 32 || row0 % 32 || K % 16) return sev_fail(SEV_EINVAL, "tensor %d: rows/K not tileable", kind);
-        if (tile_mul == 1) tile_add = row0 / 32;
-        launch_pack_bf16((uint16_t *)(m->arena + off), (const uint16_t *)src, rows, K, tile_mul, tile_add, st);
+        launch_pack_bf16((uint16_t *)(m->arena + off), (const uint16_t *)src, rows, K, mode, mode == 0 ? row0 / 32 : 0, st);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sev_fail(SEV_EHIP, "load_tensor: %s", hipGetErrorString(e));
@@ -486,9 +485,12 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     for (int b = 0; b < pa.B; ++b) total_pages += (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE;
     int64_t total_groups = 0;
     for (int b = 0; b < pa.B; ++b) total_groups += (G * pa.nd[b] + 31) / 32;
-    const int64_t want_items = 1024 / std::max(1, d.n_kv_heads);
-    int64_t cp = std::max<int64_t>(8, total_pages * std::max<int64_t>(1, total_groups / pa.B) / std::max<int64_t>(1, want_items));
-    cp = std::min<int64_t>(cp, 64);
+    // a block of 4 waves takes alternate page pairs of its chunk: aim for >= 4 pairs per wave (32 pages)
+    // unless that leaves fewer than ~2 blocks per compute unit; never below 8 pages
+    const int64_t blocks_at_32 = (total_pages / 32 + pa.B) * std::max<int64_t>(1, total_groups / pa.B) * d.n_kv_heads;
+    int64_t cp = 32;
+    if (blocks_at_32 < 512) cp = 16;
+    if (blocks_at_32 < 128) cp = 8;
     for (;; cp *= 2) {
         int64_t items = 0;
         for (int b = 0; b < pa.B; ++b) {

@@ -150,6 +150,6 @@ void launch_pack_f32(float *dst, const float *src, int64_t n, hipStream_t st);
 void f32_forward(const sev_model *m, sev_kv *kv, int rows, int B, float *logits_out, hipStream_t st);
 
 // bf16 path
-void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int tile_mul, int tile_add, hipStream_t st);
+void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int mode, int tile_add, hipStream_t st);
 void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, float *logits_out,
                   hipStream_t st);
