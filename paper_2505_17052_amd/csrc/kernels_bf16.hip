@@ -6,9 +6,12 @@
 // MFMAs that accumulate into the same float32 registers; the residual stream, norms, rotary
 // embedding, softmax and all accumulations are float32.  (A single bf16 plane per activation
 // accumulates ~3 % relative error over 32 layers; the split keeps it near 1e-5.)
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "sev_internal.h"
 #include "kv_layout.h"
@@ -35,15 +38,25 @@ __device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo) 
     lo = f32_to_bf16_bits(x - bf16_bits_to_f32(hi));
 }
 
+// hi/lo split of two floats at once with the packed hardware conversion (round to nearest even):
+// hi = {bf16(a), bf16(b)}, lo = {bf16(a - hi_a), bf16(b - hi_b)}, element 0 in the low half.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void split_pack2(float a, float b, uint32_t &hi, uint32_t &lo) {
+    const f32x2 v = {a, b};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    const bf16x2 l = __builtin_convertvector(v - __builtin_convertvector(h, f32x2), bf16x2);
+    hi = __builtin_bit_cast(uint32_t, h);
+    lo = __builtin_bit_cast(uint32_t, l);
+}
+
 // Writes 8 consecutive-k activations of row m (k0 a multiple of 8) as hi and lo fragments.
 __device__ __forceinline__ void store_split8(uint16_t *xp, int m, int k0, int m_tiles, const float *v) {
-    uint32_t h[8], l[8];
+    uint32_t h[4], l[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) split_bf16(v[i], h[i], l[i]);
-    uint4 H = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    uint4 Lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
-    *(uint4 *)(xp + xpack_index(m, k0, 0, m_tiles)) = H;
-    *(uint4 *)(xp + xpack_index(m, k0, 1, m_tiles)) = Lo;
+    for (int i = 0; i < 4; ++i) split_pack2(v[2 * i], v[2 * i + 1], h[i], l[i]);
+    *(uint4 *)(xp + xpack_index(m, k0, 0, m_tiles)) = make_uint4(h[0], h[1], h[2], h[3]);
+    *(uint4 *)(xp + xpack_index(m, k0, 1, m_tiles)) = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -174,7 +187,7 @@ __global__ __launch_bounds__(1024) void resid_norm_kernel(float *h, const float 
 // planes, already in fragment order) go global -> LDS once per block and are shared by the 4 waves.
 // MFMA 32x32x16: A = weight tile (32 n x 16 k), B = activation tile (16 k x 32 m), so a lane ends up
 // with 4 consecutive output columns of one row per register quad (vector stores along N).
-// grid: x = column groups, y = split-K slices, z = blocks of 128 rows.
+// grid: 1-D over (column group, split-K slice, row block of MT tiles); see the block index decode.
 // ---------------------------------------------------------------------------
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
 
@@ -182,6 +195,7 @@ struct GemmArgs {
     const uint4 *W;          // re-tiled weights
     const uint4 *X;          // xpack activations
     int n_tiles, k_steps, m_tiles_total, M, N;
+    int col_groups, m_blocks, splits;   // grid decomposition (see the kernel's block index decode)
     float *part;             // EPI_PARTIAL: [S][M][N]
     uint16_t *act;           // EPI_SWIGLU: xpack with K = N/2 (N counts gate and up rows)
     float *lm_val;           // EPI_ARGMAX: [gridDim.x*4][lm_stride]
@@ -195,11 +209,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     extern __shared__ u32x4 xs[];                       // [2 buffers][2 k-steps][MT][2 planes][64 lanes]
     constexpr int STAGE_U4 = 2 * MT * 2 * 64;           // uint4 per stage
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tile0 = (blockIdx.x * 4 + wave) * NT;
-    const int mt0 = blockIdx.z * 4;
+    // Block index decode, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, each with its
+    // own L2.  Blocks that re-read the same weight tiles (the row blocks of one column group) get ids 8
+    // apart, i.e. land on the same XCD back to back, so the second read hits that L2.
+    int q = blockIdx.x >> 3;
+    const int mb = q % g.m_blocks;
+    q /= g.m_blocks;
+    const int split = q % g.splits;
+    const int cg = (q / g.splits) * 8 + (blockIdx.x & 7);
+    if (cg >= g.col_groups) return;                      // whole block leaves before any barrier
+    const int tile0 = (cg * 4 + wave) * NT;
+    const int mt0 = mb * MT;
     const int n_stages = g.k_steps >> 1;
-    const int s_begin = (int)((int64_t)n_stages * blockIdx.y / gridDim.y);
-    const int s_end = (int)((int64_t)n_stages * (blockIdx.y + 1) / gridDim.y);
+    const int s_begin = (int)((int64_t)n_stages * split / g.splits);
+    const int s_end = (int)((int64_t)n_stages * (split + 1) / g.splits);
     const int n = s_end - s_begin;
 
     f32x16 acc[NT][MT];
@@ -311,7 +334,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // ------------------------------------------------------------------ epilogues
     const int mrow = lane & 31, nsub = 4 * (lane >> 5);
     if constexpr (EPI == EPI_PARTIAL) {
-        float *out = g.part + (size_t)blockIdx.y * g.M * g.N;
+        float *out = g.part + (size_t)split * g.M * g.N;
 #pragma unroll
         for (int a = 0; a < NT; ++a) {
             if (tile0 + a >= g.n_tiles) continue;
@@ -338,16 +361,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                 if (m >= g.M) continue;
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj) {
-                    uint32_t hi[4], lo[4];
+                    float v[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const float gt = acc[a][b][8 * jj + r], up = acc[a][b][8 * jj + 4 + r];
-                        const float v = gt / (1.0f + __expf(-gt)) * up;
-                        split_bf16(v, hi[r], lo[r]);
+                        v[r] = gt / (1.0f + __expf(-gt)) * up;
                     }
+                    uint32_t hi[2], lo[2];
+                    split_pack2(v[0], v[1], hi[0], lo[0]);
+                    split_pack2(v[2], v[3], hi[1], lo[1]);
                     const int f0 = (tile0 + a) * 16 + 8 * jj + nsub;
-                    *(uint2 *)(g.act + xpack_index(m, f0, 0, g.m_tiles_total)) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
-                    *(uint2 *)(g.act + xpack_index(m, f0, 1, g.m_tiles_total)) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+                    *(uint2 *)(g.act + xpack_index(m, f0, 0, g.m_tiles_total)) = make_uint2(hi[0], hi[1]);
+                    *(uint2 *)(g.act + xpack_index(m, f0, 1, g.m_tiles_total)) = make_uint2(lo[0], lo[1]);
                 }
             }
         }
@@ -378,7 +403,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             const int oi = __shfl_xor(bi, 32);
             if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
             if (lane < 32 && m < g.M) {
-                const size_t slot = (size_t)(blockIdx.x * 4 + wave) * g.lm_stride + m;
+                const size_t slot = (size_t)(cg * 4 + wave) * g.lm_stride + m;
                 g.lm_val[slot] = bv;
                 g.lm_idx[slot] = bi;
             }
@@ -475,41 +500,51 @@ __global__ __launch_bounds__(64) void rope_kv_bf16_kernel(const float *part, int
 // LDS and written out for the cross-chunk merge.  Masking: keys < P are visible to every row;
 // key P + j is visible to a row iff bit j of the row's ancestor mask is set.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g,
-                                                        const int32_t *page_table, int max_pages, int layer, int Hq,
-                                                        float *att_o, float2 *att_ml, float scale_log2e) {
-    extern __shared__ float lds[];                    // two merge slots: 64 accumulator registers + max + sum per lane
+__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g, int layer, int Hq,
+                                                           float *att_o, float2 *att_ml, float scale_log2e) {
+    extern __shared__ float lds[];                    // two merge slots (64 accumulator registers + max + sum per lane), then the q fragments
     const int item = blockIdx.x, kvh = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int b = p.it_req[item], rg = p.it_rg[item], page0 = p.it_page0[item], npages = p.it_npages[item];
-    const int P = p.req_P[b], n = p.req_n[b], row0 = p.req_row0[b], slot = p.req_slot[b];
+    // everything the block needs to know comes from two 16-byte loads and one page-id load, all independent
+    const int4 ia = p.it_a[item], ib = p.it_b[item];
+    const int rg = ia.x, page0 = ia.y, npages = ia.z, P = ia.w, n = ib.x, row0 = ib.y;
+    const int npairs = (npages + 1) >> 1;
+    const int my_pairs = npairs > wave ? (npairs - wave + 3) >> 2 : 0;       // this wave takes pairs wave, wave+4, ...
+    int pt_val;                                         // lane j < 32: page (j&1) of this wave's pair j/2
+    {
+        const int pidx = 2 * (wave + 4 * ((lane & 31) >> 1)) + (lane & 1);
+        pt_val = p.it_pages[(size_t)item * SEV_ATT_MAX_CP + min(pidx, npages - 1)];
+    }
     const int G = Hq / g.Hkv;
     const int qi = lane & 15, grp = lane >> 4;
-    const int32_t *pt = page_table + (size_t)slot * max_pages;
-    const char *Kl = g.pool + (size_t)layer * g.layer_stride;
+    const char *Kl = g.pool + (size_t)layer * g.layer_stride + (size_t)kvh * 4096 + lane * 16;
     const char *Vl = Kl + g.v_offset;
+    const size_t page_stride = (size_t)g.Hkv * 4096;
     const size_t qd = (size_t)Hq * 128;
 
-    // query fragments (B operand: lane (q = lane%16, c = lane/16) holds dims 32*step + 8c .. +7)
-    bf16x8 qf[2][2][4];
+    // Query fragments go to LDS once per block, in B-operand order [plane][q tile][k step][lane]
+    // (lane (q = lane%16, c = lane/16) holds dims 32*step + 8c .. +7 of row q); every wave re-reads them
+    // per page pair, which keeps 64 registers free for a second resident block per compute unit.
+    u32x4 *qs = (u32x4 *)(lds + 2 * 64 * 64 + 2 * 2 * 2 * 64);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = threadIdx.x + 256 * i;            // 0..1023 = [pl 2][qt 2][st 4][lane 64]
+        const int ln = e & 63, st = (e >> 6) & 3, qt = (e >> 8) & 1, pl = e >> 9;
+        const int R = rg * 32 + qt * 16 + (ln & 15);
+        u32x4 v = (u32x4){0u, 0u, 0u, 0u};
+        if (R < G * n) {
+            const int hg = R / n, node = R - hg * n;
+            v = *(const u32x4 *)(q_planes + (size_t)pl * M * qd + (size_t)(row0 + node) * qd + (size_t)(kvh * G + hg) * 128 +
+                                 8 * (ln >> 4) + 32 * st);
+        }
+        qs[e] = v;
+    }
     unsigned long long anc[2];
-    bool rvalid[2];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         const int R = rg * 32 + qt * 16 + qi;
-        rvalid[qt] = R < G * n;
-        const int hg = rvalid[qt] ? R / n : 0, node = rvalid[qt] ? R - hg * n : 0;
-        const int m = row0 + node;
-        anc[qt] = rvalid[qt] ? p.row_anc[m] : 0ull;
-        const size_t o = (size_t)m * qd + (size_t)(kvh * G + hg) * 128 + 8 * grp;
-#pragma unroll
-        for (int pl = 0; pl < 2; ++pl)
-#pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (rvalid[qt]) v = *(const uint4 *)(q_planes + (size_t)pl * M * qd + o + 32 * st);
-                qf[pl][qt][st] = as_bf16x8(v);
-            }
+        anc[qt] = 0ull;
+        if (R < G * n) anc[qt] = p.row_anc[row0 + R % n];
     }
 
     f32x4 oacc[8][2];
@@ -519,81 +554,99 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *q_planes
         for (int qt = 0; qt < 2; ++qt) oacc[t][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
 
-    const int npairs = (npages + 1) >> 1;
-    for (int pp = wave; pp < npairs; pp += 4) {
-        const int lp0 = page0 + 2 * pp;                     // logical pages of the pair
-        const bool has1 = (2 * pp + 1) < npages;
-        const size_t blk0 = ((size_t)pt[lp0] * g.Hkv + kvh) * 4096;
-        const size_t blk1 = ((size_t)pt[has1 ? lp0 + 1 : lp0] * g.Hkv + kvh) * 4096;
-        uint4 k0[4], k1[4], v0[4], v1[4];
+    // K and V of a page pair live in one register set each; the next pair's keys are requested as soon
+    // as the score MFMAs have consumed the current ones, the next values right after the PV MFMAs, so
+    // both latencies hide behind the other half of the pair's work.
+    u32x4 k0[4], k1[4], v0[4], v1[4];
+    auto load_k = [&](int i) {
+        const char *a0 = Kl + (size_t)__shfl(pt_val, 2 * i) * page_stride, *a1 = Kl + (size_t)__shfl(pt_val, 2 * i + 1) * page_stride;
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            k0[st] = *(const uint4 *)(Kl + blk0 + st * 1024 + lane * 16);
-            k1[st] = *(const uint4 *)(Kl + blk1 + st * 1024 + lane * 16);
+            k0[st] = *(const u32x4 *)(a0 + st * 1024);
+            k1[st] = *(const u32x4 *)(a1 + st * 1024);
         }
+    };
+    auto load_v = [&](int i) {
+        const char *a0 = Vl + (size_t)__shfl(pt_val, 2 * i) * page_stride, *a1 = Vl + (size_t)__shfl(pt_val, 2 * i + 1) * page_stride;
 #pragma unroll
         for (int tp = 0; tp < 4; ++tp) {
-            v0[tp] = *(const uint4 *)(Vl + blk0 + tp * 1024 + lane * 16);
-            v1[tp] = *(const uint4 *)(Vl + blk1 + tp * 1024 + lane * 16);
+            v0[tp] = *(const u32x4 *)(a0 + tp * 1024);
+            v1[tp] = *(const u32x4 *)(a1 + tp * 1024);
         }
+    };
+    if (my_pairs > 0) {
+        load_k(0);
+        load_v(0);
+    }
+    __syncthreads();                                       // q fragments are in LDS
+
+    auto pair_step = [&](int i, auto prefetch_tag) {
+        constexpr bool PREFETCH = decltype(prefetch_tag)::value;
+        const int lp0 = 2 * (wave + 4 * i);                 // chunk-local pages of the pair
+        const bool has1 = (lp0 + 1) < npages;
         // scores: s[page][qt] holds keys 4*grp + r of the page for query qi
         f32x4 s[2][2];
 #pragma unroll
-        for (int pg = 0; pg < 2; ++pg)
+        for (int qt = 0; qt < 2; ++qt) {
+            f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int st = 0; st < 4; ++st) {
-                    const bf16x8 kf = as_bf16x8(pg ? k1[st] : k0[st]);
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[0][qt][st], a, 0, 0, 0);
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[1][qt][st], a, 0, 0, 0);
-                }
-                s[pg][qt] = a;
+            for (int st = 0; st < 4; ++st) {
+                const bf16x8 qh = as_bf16x8(qs[((0 * 2 + qt) * 4 + st) * 64 + lane]);
+                const bf16x8 ql = as_bf16x8(qs[((1 * 2 + qt) * 4 + st) * 64 + lane]);
+                a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0[st]), qh, a0, 0, 0, 0);
+                a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1[st]), qh, a1, 0, 0, 0);
+                a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0[st]), ql, a0, 0, 0, 0);
+                a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1[st]), ql, a1, 0, 0, 0);
             }
-        const int key0 = lp0 * 16 + 4 * grp;                // first key of this lane in page 0 of the pair
-        const bool need_mask = (lp0 + 2) * 16 > P || !has1;
+            s[0][qt] = a0;
+            s[1][qt] = a1;
+        }
+        if (PREFETCH) load_k(i + 1);
+        const int j0 = (page0 + lp0) * 16 + 4 * grp - P;    // draft-node index of this lane's first key (negative: prefix)
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
+            uint32_t h[4], l[4];
             float mx = -INFINITY;
 #pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
+            for (int pg = 0; pg < 2; ++pg) {
+                // 4-bit visibility of keys j..j+3: prefix keys (index < 0) always, draft key i iff ancestor bit i
+                // (the mask has no bits at or above n); plain shifts, no branches
+                const int j = j0 + pg * 16;
+                const unsigned long long m = anc[qt];
+                const unsigned up = j < 64 ? (unsigned)(m >> max(j, 0)) : 0u;               // j >= 0 (the tail of the last page can reach past 63)
+                const unsigned dn = (unsigned)((m << (-max(j, -3))) | ((1ull << (-max(j, -3))) - 1ull));   // -3 <= j < 0
+                unsigned vis4 = j >= 0 ? up : (j <= -4 ? 0xFu : dn);
+                if (pg == 1 && !has1) vis4 = 0u;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float v = s[pg][qt][r] * scale_log2e;
-                    if (need_mask) {
-                        const int key = key0 + pg * 16 + r;
-                        bool vis = key < P || (key - P < n && ((anc[qt] >> (key - P)) & 1ull));
-                        if (pg && !has1) vis = false;
-                        if (!vis) v = -INFINITY;
-                    }
+                    const float v = ((vis4 >> r) & 1u) ? s[pg][qt][r] * scale_log2e : -INFINITY;
                     s[pg][qt][r] = v;
                     mx = fmaxf(mx, v);
                 }
+            }
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float mnew = fmaxf(mrun[qt], mx);
             const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = exp2f(mrun[qt] - muse);
+            const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - muse);
             mrun[qt] = mnew;
             float ps = 0.f;
-            uint32_t ph[8], plo[8];
 #pragma unroll
             for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float pv = exp2f(s[pg][qt][r] - muse);
-                    ps += pv;
-                    split_bf16(pv, ph[pg * 4 + r], plo[pg * 4 + r]);
+                for (int r = 0; r < 4; r += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(s[pg][qt][r] - muse), p1 = __builtin_amdgcn_exp2f(s[pg][qt][r + 1] - muse);
+                    ps += p0 + p1;
+                    split_pack2(p0, p1, h[pg * 2 + r / 2], l[pg * 2 + r / 2]);
                 }
             lrun[qt] = lrun[qt] * alpha + ps;
-            const bf16x8 pH = as_bf16x8(make_uint4(ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16), ph[4] | (ph[5] << 16), ph[6] | (ph[7] << 16)));
-            const bf16x8 pL = as_bf16x8(make_uint4(plo[0] | (plo[1] << 16), plo[2] | (plo[3] << 16), plo[4] | (plo[5] << 16), plo[6] | (plo[7] << 16)));
+            const bf16x8 pH = as_bf16x8((u32x4){h[0], h[1], h[2], h[3]});
+            const bf16x8 pL = as_bf16x8((u32x4){l[0], l[1], l[2], l[3]});
 #pragma unroll
             for (int tp = 0; tp < 4; ++tp) {
                 // dims tile 2tp: tokens from the low halves of the two pages' loads; tile 2tp+1: high halves
-                const bf16x8 va = as_bf16x8(make_uint4(v0[tp].x, v0[tp].y, v1[tp].x, v1[tp].y));
-                const bf16x8 vb = as_bf16x8(make_uint4(v0[tp].z, v0[tp].w, v1[tp].z, v1[tp].w));
+                const bf16x8 va = as_bf16x8((u32x4){v0[tp][0], v0[tp][1], v1[tp][0], v1[tp][1]});
+                const bf16x8 vb = as_bf16x8((u32x4){v0[tp][2], v0[tp][3], v1[tp][2], v1[tp][3]});
                 f32x4 oa = oacc[2 * tp][qt], ob = oacc[2 * tp + 1][qt];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) { oa[r] *= alpha; ob[r] *= alpha; }
@@ -605,7 +658,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const uint16_t *q_planes
                 oacc[2 * tp + 1][qt] = ob;
             }
         }
-    }
+        if (PREFETCH) load_v(i + 1);
+    };
+    for (int i = 0; i + 1 < my_pairs; ++i) pair_step(i, std::true_type{});
+    if (my_pairs > 0) pair_step(my_pairs - 1, std::false_type{});
 
     // ---- merge the 4 waves pairwise through LDS, in the accumulators' own register layout
     // (wave 1 -> 0 and 3 -> 2, then 2 -> 0); wave 0 writes the block's partial result.
@@ -699,42 +755,63 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float *att_o, con
 // ---------------------------------------------------------------------------
 // host orchestration of one forward pass
 // ---------------------------------------------------------------------------
-#define GU_NT 1   // column tiles per wave in the gate/up GEMM
-
-struct GemmPlan {
-    int NT, S;
+struct GemmCfg {
+    int MT, NT, S, PF;
 };
 
-static GemmPlan plan_gemm(int n_tiles, int k_steps, int rows, size_t part_elems, int N, bool allow_split) {
-    GemmPlan gp;
-    const int n_stages = k_steps / 2;
-    int ctas2 = (n_tiles + 7) / 8;
-    gp.NT = (ctas2 >= 192 && n_tiles % 2 == 0) ? 2 : 1;
-    const int ctas = (n_tiles + 4 * gp.NT - 1) / (4 * gp.NT);
-    int S = 1;
-    if (allow_split) {
-        S = (256 + ctas - 1) / ctas;
-        S = std::min(S, 8);
-        S = std::min(S, std::max(1, n_stages / 8));
-        while (S > 1 && (size_t)S * rows * N > part_elems) --S;
+enum { G_QKV = 0, G_O, G_GU, G_DOWN, G_LM };
+
+// Tile configuration of one GEMM.  Row tiles per block MT (weights are re-read through L2 by each row
+// block), column tiles per wave NT, split-K slices S, prefetch depth PF.  Environment variables
+// SEV_TUNE_QKV / _O / _GU / _DOWN / _LM = "MT,NT,S,PF" override the choice (tuning experiments).
+static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, int rows, size_t part_elems, int N) {
+    static const char *names[] = {"SEV_TUNE_QKV", "SEV_TUNE_O", "SEV_TUNE_GU", "SEV_TUNE_DOWN", "SEV_TUNE_LM"};
+    GemmCfg c;
+    c.MT = m_tiles >= 2 ? 2 : 1;
+    c.NT = (n_tiles % 2 == 0) ? 2 : 1;
+    c.PF = 4;
+    c.S = 1;
+    const bool splittable = which == G_QKV || which == G_O || which == G_DOWN;
+    if (splittable) {
+        const int m_blocks = (m_tiles + c.MT - 1) / c.MT;
+        const int blocks = ((n_tiles + 4 * c.NT - 1) / (4 * c.NT)) * m_blocks;
+        c.S = std::min(8, std::max(1, (256 + blocks - 1) / blocks));
+        c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));
     }
-    gp.S = std::max(S, 1);
-    return gp;
+    if (const char *e = getenv(names[which])) {
+        int mt, nt, sp, pf;
+        if (sscanf(e, "%d,%d,%d,%d", &mt, &nt, &sp, &pf) == 4 && (mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2) &&
+            sp >= 1 && sp <= 16 && (pf == 4 || (pf == 6 && mt <= 2))) {
+            c.MT = std::min(mt, m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1));
+            c.NT = nt;
+            c.PF = pf;
+            if (splittable) c.S = sp;
+        }
+    }
+    if (!splittable) c.S = 1;
+    c.S = std::min(c.S, std::max(1, k_steps / 2));
+    while (c.S > 1 && (size_t)c.S * rows * N > part_elems) --c.S;
+    return c;
 }
 
 template <int EPI>
-static void launch_gemm(const GemmArgs &ga, int NT, int S, int m_tiles, hipStream_t st) {
-    const int mblocks = (m_tiles + 3) / 4;
-    const int MT = m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1);
-    dim3 grid((ga.n_tiles + 4 * NT - 1) / (4 * NT), S, mblocks);
-    const size_t lds = (size_t)2 * 2 * MT * 2 * 64 * 16;
-#define SEV_LAUNCH(MT_, NT_)                                                                                          \
-    hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, 4>), grid, dim3(256), lds, st, ga)
-    if (NT == 2) {
-        if (MT == 4) SEV_LAUNCH(4, 2); else if (MT == 2) SEV_LAUNCH(2, 2); else SEV_LAUNCH(1, 2);
-    } else {
-        if (MT == 4) SEV_LAUNCH(4, 1); else if (MT == 2) SEV_LAUNCH(2, 1); else SEV_LAUNCH(1, 1);
-    }
+static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t st) {
+    ga.col_groups = (ga.n_tiles + 4 * c.NT - 1) / (4 * c.NT);
+    ga.m_blocks = (m_tiles + c.MT - 1) / c.MT;
+    ga.splits = c.S;
+    const int g8 = (ga.col_groups + 7) / 8 * 8;
+    dim3 grid((unsigned)(g8 * ga.m_blocks * ga.splits));
+    const size_t lds = (size_t)2 * 2 * c.MT * 2 * 64 * 16;
+#define SEV_LAUNCH(MT_, NT_, PF_)                                                                                     \
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, PF_>), grid, dim3(256), lds, st, ga)
+#define SEV_BY_NT(MT_, PF_)                                                                                           \
+    do {                                                                                                              \
+        if (c.NT == 2) SEV_LAUNCH(MT_, 2, PF_); else SEV_LAUNCH(MT_, 1, PF_);                                         \
+    } while (0)
+    if (c.MT == 4) SEV_BY_NT(4, 4);
+    else if (c.MT == 2) { if (c.PF == 6) SEV_BY_NT(2, 6); else SEV_BY_NT(2, 4); }
+    else { if (c.PF == 6) SEV_BY_NT(1, 6); else SEV_BY_NT(1, 4); }
+#undef SEV_BY_NT
 #undef SEV_LAUNCH
 }
 
@@ -755,9 +832,11 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         hipLaunchKernelGGL(embed_norm_kernel, dim3(rows), dim3(256), 0, st, (const uint16_t *)(m->arena + m->off_embed),
                            kv->plan.row_tok, Gp(m->layers[0].g_attn), kv->h, xa, d.d_model, m_tiles, d.rms_eps);
     }
-    const GemmPlan pq = plan_gemm(m->n_qkv / 32, d.d_model / 16, rows, kv->part_elems, m->n_qkv, true);
-    const GemmPlan po = plan_gemm(d.d_model / 32, m->q_dim / 16, rows, kv->part_elems, d.d_model, true);
-    const GemmPlan pd = plan_gemm(d.d_model / 32, d.d_ffn / 16, rows, kv->part_elems, d.d_model, true);
+    const GemmCfg pq = choose_cfg(G_QKV, m_tiles_real, m->n_qkv / 32, d.d_model / 16, rows, kv->part_elems, m->n_qkv);
+    const GemmCfg po = choose_cfg(G_O, m_tiles_real, d.d_model / 32, m->q_dim / 16, rows, kv->part_elems, d.d_model);
+    const GemmCfg pg = choose_cfg(G_GU, m_tiles_real, d.d_ffn / 16, d.d_model / 16, rows, kv->part_elems, 2 * d.d_ffn);
+    const GemmCfg pd = choose_cfg(G_DOWN, m_tiles_real, d.d_model / 32, d.d_ffn / 16, rows, kv->part_elems, d.d_model);
+    const GemmCfg pl = choose_cfg(G_LM, m_tiles_real, d.vocab / 32, d.d_model / 16, rows, kv->part_elems, d.vocab);
     for (int l = 0; l < d.n_layers; ++l) {
         const LayerOffsets &lo = m->layers[l];
         GemmArgs ga;
@@ -768,7 +847,7 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             Prof p(kv, st, PROF_GEMM_QKV);
             ga.W = Wp(lo.wqkv); ga.X = (const uint4 *)xa; ga.n_tiles = m->n_qkv / 32; ga.k_steps = d.d_model / 16;
             ga.N = m->n_qkv; ga.part = kv->part;
-            launch_gemm<EPI_PARTIAL>(ga, pq.NT, pq.S, m_tiles_real, st);
+            launch_gemm<EPI_PARTIAL>(ga, pq, m_tiles_real, st);
         }
         {
             Prof p(kv, st, PROF_OTHER);
@@ -777,9 +856,9 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         }
         {
             Prof p(kv, st, PROF_ATTN);
-            const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 2 * 64) * 4;
-            hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan, g,
-                               kv->page_table, kv->max_pages_per_req, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e);
+            const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 2 * 64) * 4 + 1024 * 16;   // merge slots + q fragments
+            hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan, g, l,
+                               d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e);
             hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
                                kv->plan, d.n_q_heads, d.n_kv_heads, op, m_tiles);
         }
@@ -787,7 +866,7 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             Prof p(kv, st, PROF_GEMM_O);
             ga.W = Wp(lo.wo); ga.X = (const uint4 *)op; ga.n_tiles = d.d_model / 32; ga.k_steps = m->q_dim / 16;
             ga.N = d.d_model; ga.part = kv->part;
-            launch_gemm<EPI_PARTIAL>(ga, po.NT, po.S, m_tiles_real, st);
+            launch_gemm<EPI_PARTIAL>(ga, po, m_tiles_real, st);
         }
         {
             Prof p(kv, st, PROF_OTHER);
@@ -798,13 +877,13 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             Prof p(kv, st, PROF_GEMM_GU);
             ga.W = Wp(lo.wgu); ga.X = (const uint4 *)xa; ga.n_tiles = d.d_ffn / 16; ga.k_steps = d.d_model / 16;
             ga.N = 2 * d.d_ffn; ga.act = act;
-            launch_gemm<EPI_SWIGLU>(ga, GU_NT, 1, m_tiles_real, st);
+            launch_gemm<EPI_SWIGLU>(ga, pg, m_tiles_real, st);
         }
         {   // down projection -> partials; residual + next norm
             Prof p(kv, st, PROF_GEMM_DOWN);
             ga.W = Wp(lo.wd); ga.X = (const uint4 *)act; ga.n_tiles = d.d_model / 32; ga.k_steps = d.d_ffn / 16;
             ga.N = d.d_model; ga.part = kv->part;
-            launch_gemm<EPI_PARTIAL>(ga, pd.NT, pd.S, m_tiles_real, st);
+            launch_gemm<EPI_PARTIAL>(ga, pd, m_tiles_real, st);
         }
         {
             Prof p(kv, st, PROF_OTHER);
@@ -820,9 +899,8 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         ga.m_tiles_total = m_tiles; ga.M = rows;
         ga.W = Wp(m->off_lm); ga.X = (const uint4 *)xa; ga.n_tiles = d.vocab / 32; ga.k_steps = d.d_model / 16; ga.N = d.vocab;
         ga.lm_val = kv->lm_val; ga.lm_idx = kv->lm_idx; ga.lm_stride = m_tiles * 32; ga.logits = logits_out;
-        const int NT = (ga.n_tiles % 2 == 0) ? 2 : 1;
-        launch_gemm<EPI_ARGMAX>(ga, NT, 1, m_tiles_real, st);
-        const int n_part = ((ga.n_tiles + 4 * NT - 1) / (4 * NT)) * 4;
+        launch_gemm<EPI_ARGMAX>(ga, pl, m_tiles_real, st);
+        const int n_part = ((ga.n_tiles + 4 * pl.NT - 1) / (4 * pl.NT)) * 4;
         hipLaunchKernelGGL(lm_reduce_kernel, dim3(rows), dim3(256), 0, st, kv->lm_val, kv->lm_idx, n_part, ga.lm_stride,
                            kv->row_argmax);
     }

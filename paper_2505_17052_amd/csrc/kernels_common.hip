@@ -39,6 +39,8 @@ struct PlanDev {
     double rope_base;
     int chunk_pages;
     const int32_t *tokens, *parents;
+    const int32_t *page_table;
+    int max_pages;
 };
 
 __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
@@ -110,10 +112,11 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
             d.p.mg_count[g0 + rg] = my_chunks;
             for (int c = 0; c < my_chunks; ++c, ++it) {
                 const int p0 = c * d.chunk_pages;
-                d.p.it_req[it] = t;
-                d.p.it_rg[it] = rg;
-                d.p.it_page0[it] = p0;
-                d.p.it_npages[it] = min(d.chunk_pages, pages - p0);
+                const int np = min(d.chunk_pages, pages - p0);
+                d.p.it_a[it] = make_int4(rg, p0, np, P);
+                d.p.it_b[it] = make_int4(n, row0, t, 0);
+                const int32_t *pt = d.page_table + (size_t)slot * d.max_pages;
+                for (int i = 0; i < np; ++i) d.p.it_pages[(size_t)it * SEV_ATT_MAX_CP + i] = pt[p0 + i];
             }
         }
     }
@@ -144,6 +147,8 @@ void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_toke
     d.chunk_pages = chunk_pages;
     d.tokens = draft_tokens;
     d.parents = parents;
+    d.page_table = kv->page_table;
+    d.max_pages = kv->max_pages_per_req;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, pa, d);
 }
 

@@ -2,6 +2,7 @@
 // launch sequence of one verification step.  All arithmetic of the method runs in the kernels.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -251,7 +252,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     const size_t o_row = take(4 * rows_pad * 4);
     const size_t o_anc = take(rows_pad * 8);
     const size_t o_cs = take(rows_pad * (d.head_dim / 2) * 8);
-    const size_t o_it = take(4 * (size_t)kv->max_items * 4);
+    const size_t o_it = take((size_t)kv->max_items * (32 + SEV_ATT_MAX_CP * 4));
     const size_t o_mg = take(4 * (size_t)kv->max_groups * 4);
     const size_t o_h = take(rows_pad * d.d_model * 4);
     const size_t o_part = take(kv->part_elems * 4);
@@ -299,11 +300,9 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->plan.row_tok = rw + 3 * rows_pad;
     kv->plan.row_anc = (unsigned long long *)(w + o_anc);
     kv->plan.row_cs = (float2 *)(w + o_cs);
-    int32_t *it = (int32_t *)(w + o_it);
-    kv->plan.it_req = it;
-    kv->plan.it_rg = it + kv->max_items;
-    kv->plan.it_page0 = it + 2 * (size_t)kv->max_items;
-    kv->plan.it_npages = it + 3 * (size_t)kv->max_items;
+    kv->plan.it_a = (int4 *)(w + o_it);
+    kv->plan.it_b = kv->plan.it_a + kv->max_items;
+    kv->plan.it_pages = (int32_t *)(kv->plan.it_b + kv->max_items);
     int32_t *mg = (int32_t *)(w + o_mg);
     kv->plan.mg_req = mg;
     kv->plan.mg_rg = mg + kv->max_groups;
@@ -485,12 +484,18 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     for (int b = 0; b < pa.B; ++b) total_pages += (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE;
     int64_t total_groups = 0;
     for (int b = 0; b < pa.B; ++b) total_groups += (G * pa.nd[b] + 31) / 32;
-    // a block of 4 waves takes alternate page pairs of its chunk: aim for >= 4 pairs per wave (32 pages)
-    // unless that leaves fewer than ~2 blocks per compute unit; never below 8 pages
-    const int64_t blocks_at_32 = (total_pages / 32 + pa.B) * std::max<int64_t>(1, total_groups / pa.B) * d.n_kv_heads;
-    int64_t cp = 32;
-    if (blocks_at_32 < 512) cp = 16;
-    if (blocks_at_32 < 128) cp = 8;
+    // a block of 4 waves takes alternate page pairs of its chunk; its fixed cost (query fragments,
+    // wave merge, partial result) is amortised over the chunk: aim for 8 pairs per wave (64 pages),
+    // but keep roughly one block per compute unit; never below 8 pages
+    int64_t cp = 64;
+    for (; cp > 8; cp /= 2) {
+        const int64_t blocks = (total_pages / cp + pa.B) * std::max<int64_t>(1, total_groups / pa.B) * d.n_kv_heads;
+        if (blocks >= 240) break;
+    }
+    if (const char *e = getenv("SEV_TUNE_CP")) {        // tuning experiments: pages per attention chunk
+        const int v = atoi(e);
+        if (v >= 2 && v <= SEV_ATT_MAX_CP) cp = v;
+    }
     for (;; cp *= 2) {
         int64_t items = 0;
         for (int b = 0; b < pa.B; ++b) {
@@ -502,7 +507,7 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
             *n_groups = (int)total_groups;
             return (int)cp;
         }
-        if (cp > (1 << 24)) return -1;
+        if (cp >= SEV_ATT_MAX_CP) return -1;
     }
 }
 

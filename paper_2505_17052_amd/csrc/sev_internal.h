@@ -7,6 +7,7 @@
 #include "../../include/sev.h"
 
 #define SEV_PAGE 16
+#define SEV_ATT_MAX_CP 128   // pages per attention work item (chunk), upper bound
 
 // ---------------------------------------------------------------------------
 // error plumbing (host)
@@ -64,8 +65,10 @@ struct DevPlan {
     int32_t *row_req, *row_node, *row_pos, *row_tok;
     unsigned long long *row_anc;
     float2 *row_cs;           // [rows][hd/2] (cos, sin) of pos * theta_i
-    // attention work items (bf16 path)
-    int32_t *it_req, *it_rg, *it_page0, *it_npages;        // [items]
+    // attention work items (bf16 path): a = {row group, first page, pages, prefix length},
+    // b = {draft nodes, first row, request, 0}; pages = physical page ids of the chunk, SEV_ATT_MAX_CP per item
+    int4 *it_a, *it_b;
+    int32_t *it_pages;
     int32_t *mg_req, *mg_rg, *mg_item0, *mg_count;         // [merge groups]
 };
 

