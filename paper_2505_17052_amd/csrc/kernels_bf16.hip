@@ -242,14 +242,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     }
     // Software pipeline.  Loads return in issue order, so a wait on one load drains every older one:
     // to keep PF stages in flight, weights AND activations are fetched PF stages ahead into registers
-    // and consumed in the order they were issued.  At stage st (slot u = st % PF):
-    //   LDS buffer st&1 holds X(st);  wreg[u] holds W(st);  xreg[u] holds X(st+1).
+    // and consumed in the order they were issued.  At the start of stage st (slot u = st % PF):
+    //   xf holds the activation fragments of stage st;  LDS buffer (st+1)&1 holds X(st+1);
+    //   wreg[u] holds W(st);  xreg[u] holds X(st+2).
+    // During the stage each fragment register is refilled from LDS with its stage st+1 contents right
+    // after its last MFMA, so the LDS reads of the next stage overlap the MFMAs of this one, and
+    // X(st+2) goes from registers into the LDS buffer that stage st no longer reads.
     // The loop body is PF stages of straight-line code (no branches), which lets the compiler's
     // wait-count bookkeeping follow the loads across the back-edge.  The slice is padded to a multiple
     // of PF stages: padded stages re-load the last stage (cached) and feed zero activations.
     static_assert(PF % 2 == 0, "LDS buffer parity must follow the slot index");
     u32x4 wreg[PF][NT][2];
     u32x4 xreg[PF][MT];
+    u32x4 xf[2][MT][2];
     const u32x4 *xsrc[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
@@ -260,14 +265,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const size_t x_stage = (size_t)2 * g.m_tiles_total * 128;      // 16-byte units per stage of all row tiles
     const int s_last = s_end - 1;
     const int n_pad = (n + PF - 1) / PF * PF;
+    const u32x4 zero4 = (u32x4){0u, 0u, 0u, 0u};
 
     {
-        u32x4 x0[MT];
+        u32x4 x0[MT], x1[MT];
 #pragma unroll
-        for (int i = 0; i < MT; ++i) x0[i] = xsrc[i][(size_t)s_begin * x_stage];
+        for (int i = 0; i < MT; ++i) {
+            x0[i] = xsrc[i][(size_t)s_begin * x_stage];
+            x1[i] = xsrc[i][(size_t)min(s_begin + 1, s_last) * x_stage];
+        }
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
-            const int sx = min(s_begin + u + 1, s_last), sw = min(s_begin + u, s_last);
+            const int sx = min(s_begin + u + 2, s_last), sw = min(s_begin + u, s_last);
 #pragma unroll
             for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
 #pragma unroll
@@ -276,25 +285,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                 for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = wp[a][(size_t)(2 * sw + ks) * 64];
         }
 #pragma unroll
-        for (int i = 0; i < MT; ++i) xs[threadIdx.x + 256 * i] = x0[i];
+        for (int i = 0; i < MT; ++i) {
+            xs[threadIdx.x + 256 * i] = x0[i];
+            xs[STAGE_U4 + threadIdx.x + 256 * i] = (1 < n) ? x1[i] : zero4;
+        }
     }
     __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int pl = 0; pl < 2; ++pl) xf[ks][b][pl] = xs[((ks * MT + b) * 2 + pl) * 64 + lane];
 
     for (int base = 0; base < n_pad; base += PF) {
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int st = base + u;
-            // all activation fragments of the stage are requested from LDS up front, so that only the
-            // first MFMA of the stage waits for an LDS round trip
-            const u32x4 *xb = xs + (u & 1) * STAGE_U4 + lane;
-            u32x4 xf[2][MT][2];
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int b = 0; b < MT; ++b)
-#pragma unroll
-                    for (int pl = 0; pl < 2; ++pl) xf[ks][b][pl] = xb[((ks * MT + b) * 2 + pl) * 64];
-            __builtin_amdgcn_sched_barrier(0);
+            const u32x4 *xnext = xs + ((u + 1) & 1) * STAGE_U4 + lane;      // X(st+1)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
@@ -305,21 +313,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][0]), acc[a][b], 0, 0, 0);
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][1]), acc[a][b], 0, 0, 0);
                     }
+                    xf[ks][b][0] = xnext[((ks * MT + b) * 2 + 0) * 64];
+                    xf[ks][b][1] = xnext[((ks * MT + b) * 2 + 1) * 64];
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
-            // next stage's activations: registers -> the other LDS buffer (zeros once past the slice end)
-            const bool live = st + 1 < n;
-            u32x4 *xd = xs + ((u + 1) & 1) * STAGE_U4 + threadIdx.x;
+            // interleave: after every NT*2 MFMAs (one fragment pair consumed) issue its two LDS refills
 #pragma unroll
-            for (int i = 0; i < MT; ++i) {
-                u32x4 v = xreg[u][i];
-                if (!live) v = (u32x4){0u, 0u, 0u, 0u};
-                xd[256 * i] = v;
+            for (int i = 0; i < 2 * MT; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2 * NT, 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // DS read
             }
             __builtin_amdgcn_sched_barrier(0);
+            // X(st+2): registers -> the LDS buffer whose fragments (stage st) were read during stage st-1
+            const bool live = st + 2 < n;
+            u32x4 *xd = xs + (u & 1) * STAGE_U4 + threadIdx.x;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
+            __builtin_amdgcn_sched_barrier(0);
             // refill this slot: activations first, then weights (the order they will be waited on)
-            const int sx = min(s_begin + st + PF + 1, s_last), sw = min(s_begin + st + PF, s_last);
+            const int sx = min(s_begin + st + PF + 2, s_last), sw = min(s_begin + st + PF, s_last);
 #pragma unroll
             for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
 #pragma unroll

@@ -233,7 +233,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->max_items = bf ? ATT_ITEMS_CAP : 1;
     kv->max_groups = bf ? (int)(rows_pad * G / 32 + SEV_MAX_BATCH) : 1;
     const size_t n_qkv = m->n_qkv;
-    kv->part_elems = rows_pad * std::max<size_t>(8 * std::max<size_t>(n_qkv, d.d_model), 2 * (size_t)d.d_ffn);
+    kv->part_elems = rows_pad * std::max<size_t>(16 * std::max<size_t>(n_qkv, d.d_model), 2 * (size_t)d.d_ffn);
 
     // carve the workspace
     size_t off = 0;

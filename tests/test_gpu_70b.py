@@ -1,0 +1,121 @@
+"""GPU parity at the Llama-3-70B shape (80 layers, d=8192, 64/8 heads of 128, FFN 28672, vocab 128256,
+bf16; ~141 GB of weights resident on the one GPU): workload "70b-chain-b32k8".
+
+The float32 oracle cannot hold this model (278 GB), so it runs ONE layer-streamed pass in which every
+weight tensor is generated once, uploaded to the GPU model and handed to the oracle, then dropped.
+In that pass the oracle processes, for a sample of the requests, the last prefix token followed by the
+k draft tokens as one causal block on top of the drawn cache prefix — identical to "append the last
+token, then verify the block" (the oracle's block-equals-sequential pin).  The GPU then fills its
+caches the usual way and verifies ALL 32 requests; the sampled ones are compared with the oracle
+(logits, arg-max, next token, accept length, bonus), the others are checked for the properties that
+hold for any input."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import verify_oracle as vo
+from tests.helpers import decision_gap_ok, announce
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_MAX, LOGIT_MEAN, GAP_MIN = 3e-2, 3e-3, 0.05
+
+
+def test_config5_70b_chain_b32_k8():
+    import paper_2505_17052_amd as sev
+    from paper_2505_17052_amd import harness
+    wl = synth.WORKLOADS["70b-chain-b32k8"]
+    shape = wl.shape
+    reqs = synth.make_requests(wl)
+    lens = [r.prefix_len for r in reqs]
+    B, k = wl.B, wl.k_max
+    t0 = time.time()
+    announce(f"config 5: {shape.name}, B={B} k={k} sum(P)={sum(lens)}")
+
+    dt = sev.SEV_BF16
+    model = sev.Model(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                      shape.vocab, shape.rope_base, shape.rms_eps, dt)
+    src = synth.WeightSource(shape, wl.seed)
+    loaded = set()
+
+    def tensor(name, layer):
+        """Generate once; upload to the GPU model; hand the widened values to the oracle."""
+        arr = src.tensor(name, layer)
+        key = (name, layer if name not in ("embed", "lm_head") else 0)
+        if key not in loaded:
+            model.load_tensor(name, layer, torch.from_numpy(arr.view(np.int16)).to("cuda").view(torch.bfloat16))
+            loaded.add(key)
+            if name == "wd" and layer % 10 == 9:
+                announce(f"  layer {layer} generated, uploaded and consumed ({time.time() - t0:.0f}s)")
+        return synth.bf16_bits_to_f32(arr)
+
+    om = vo.Model(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab,
+                  shape.rope_base, shape.rms_eps, tensor=tensor, dtype=np.float32, cache_weights=False, kv_bf16=True)
+
+    # drafts: random ids (the target's own prediction is unknown before the pass)
+    drafts = np.stack([r.random_tokens[:k] for r in reqs]).astype(np.int32)
+    order = np.argsort(lens)
+    sample = sorted({int(order[0]), int(order[-1]), int(order[B // 2])})
+    caches = []
+    for b in sample:
+        c = vo.Cache(om, lens[b] + k + 1)
+        for l in range(shape.n_layers):
+            K, V = synth.synthetic_kv(shape, wl.seed, b, l, lens[b] - 1)
+            c.K[l][:lens[b] - 1] = synth.bf16_bits_to_f32(K)
+            c.V[l][:lens[b] - 1] = synth.bf16_bits_to_f32(V)
+        c.length = lens[b] - 1
+        caches.append(c)
+    announce(f"  oracle caches for sample {sample} (lens {[lens[b] for b in sample]}) ({time.time() - t0:.0f}s)")
+    blocks = [np.concatenate([[int(reqs[b].prefix_tokens[-1])], drafts[b]]) for b in sample]
+    logits, _, _ = vo.forward_blocks(om, caches, blocks, [vo.chain_parents(k + 1)] * len(sample))
+    torch.cuda.synchronize()
+    assert len(loaded) == 2 + 7 * shape.n_layers
+    announce(f"  oracle pass done, GPU model loaded ({time.time() - t0:.0f}s)")
+
+    batch = harness.Batch(model, shape, [P + k + 16 for P in lens], max_rows=B * k, seed=wl.seed)
+    batch.fill_synthetic(wl.seed, lens, [int(r.prefix_tokens[-1]) for r in reqs])
+    announce(f"  GPU caches filled ({time.time() - t0:.0f}s)")
+    nts = [batch.kv.get_state(b)[1] for b in range(B)]
+    ora = {}
+    for i, b in enumerate(sample):
+        lg = logits[i]
+        top2 = np.sort(lg[0])[-2:]
+        nt_o = int(np.argmax(lg[0]))
+        if top2[1] - top2[0] >= GAP_MIN:
+            assert nts[b] == nt_o, f"request {b}: next token after the cache fill"
+        am = np.argmax(lg[1:], axis=-1)
+        part = np.partition(lg[1:], -2, axis=-1)[:, -2:]
+        a, bonus, path = vo.accept_chain(drafts[b], nt_o, am)
+        ora[b] = (lg[1:], am, part[:, 1] - part[:, 0], nt_o, a, bonus, path)
+        nts[b] = nt_o
+    batch.kv.set_state(None, lens, nts)
+    out = sev.verify_ex(model, batch.kv, lens, torch.tensor(drafts, device="cuda"), k, want_path=True, want_argmax=True,
+                        want_logits=True)
+    torch.cuda.synchronize()
+    assert batch.kv.get_state(0)[2] == 0
+    lg_gpu = out["logits"].cpu().numpy().reshape(B, k, -1)
+    am_gpu = out["row_argmax"].cpu().numpy().reshape(B, k)
+    acc, bon = out["accept_len"].cpu().numpy(), out["bonus_token"].cpu().numpy()
+    worst, mean = 0.0, 0.0
+    for b in sample:
+        lg, am, gap, nt_o, a, bonus, path = ora[b]
+        diff = np.abs(lg_gpu[b] - lg)
+        worst, mean = max(worst, float(diff.max())), max(mean, float(diff.mean()))
+        firm = gap >= GAP_MIN
+        assert np.array_equal(am_gpu[b][firm], am[firm]), f"request {b}"
+        if all(gap[i] >= GAP_MIN for i in path):
+            assert (int(acc[b]), int(bon[b])) == (a, bonus), f"request {b}"
+    announce(f"  sample logits max-abs {worst:.2e} mean-abs {mean:.2e} ({time.time() - t0:.0f}s)")
+    assert worst < LOGIT_MAX and mean < LOGIT_MEAN
+    for b in range(B):                                   # the acceptance walk, recomputed from the GPU's own arg-max
+        want, j = nts[b], 0
+        while j < k and drafts[b, j] == want:
+            want = am_gpu[b, j]
+            j += 1
+        assert (int(acc[b]), int(bon[b])) == (j, int(want)), f"request {b}"
+    sev.kv_commit(batch.kv, None, B)
+    for b in (0, B - 1):
+        assert batch.kv.get_state(b)[:2] == (lens[b] + int(acc[b]), int(bon[b]))
