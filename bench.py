@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--workload", default="8b-chain-b16k8")
     ap.add_argument("--layers", type=int, default=0, help="truncate the model (debugging only; result is then not the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (a kernel of known HBM traffic, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -81,6 +83,13 @@ def main():
         sev.kv_commit(batch.kv, None, B)
         batch.kv.set_state(None, lens, nt0)
 
+    if args.calibration_copy:
+        src_t = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda")
+        dst_t = torch.empty_like(src_t)
+        for _ in range(3):
+            dst_t.copy_(src_t)
+        torch.cuda.synchronize()
+        del src_t, dst_t
     batch.kv.set_state(None, lens, nt0)
     log(f"warm-up {args.warmup}, timing {args.steps} steps  ({time.time() - t0:.0f}s)")
     for _ in range(args.warmup):
@@ -119,6 +128,9 @@ def main():
     achieved = gu_bytes / (gu_avg_ms * 1e-3) / 1e9
     step_bytes = shape.streamed_params() * 2 + sum(P + k for P in lens) * shape.kv_bytes_per_token()
     tokens = B * k
+    # HBM bytes per gate/up launch from the rocprofv3 FETCH_SIZE and WRITE_SIZE runs kept under profiles/
+    # (KiB per dispatch x the factor a plain 1 GiB copy gives each counter); they hold for this one launch shape
+    traffic = (122969.5 * 2.0 + 7168.0 * 1.0) * 1024.0 if (wl.name == "8b-chain-b16k8" and not os.environ.get("SEV_TUNE_GU")) else None
     out = {
         "metric": "verified draft tokens/sec on 1 MI355X (8B-shape bf16, B=16, k=8); % roofline",
         "value": tokens / (ms_per_step * 1e-3),
@@ -130,7 +142,7 @@ def main():
                    "sum_prefix_tokens": int(sum(lens)), "page_size": 16,
                    "mean_accept_len": float(accept.mean()), "precision": "bf16 weights/KV, split-bf16 activations, f32 accumulate"},
         "roofline": {"bound": "hbm", "kernel": "gemm_gate_up_swiglu", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
-                     "frac": achieved / 8000.0, "traffic": None, "bytes_per_launch": gu_bytes,
+                     "frac": achieved / 8000.0, "traffic": traffic, "bytes_per_launch": gu_bytes,
                      "avg_launch_ms": gu_avg_ms, "launches_timed": gu_n,
                      "ms_per_step_with_events": (t4 - t3) * 1e3 / args.steps},
         "step_roofline": {"algorithmic_bytes_per_step": step_bytes, "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
