@@ -83,6 +83,10 @@ __device__ __forceinline__ float block_sum(float v, float *red) {
 // [16t, 16t+16) of BOTH matrices, 4-row groups alternating so that an MFMA output lane owns the
 // gate and the up value of the same 4 columns: tile row n = 8j + 4h + r (j = 0..3, h = 0..1, r = 0..3)
 // is the gate (j even) or up (j odd) row 16t + 8(j/2) + 4h + r.
+// mode 3 (q, k, v projections, head_dim 128): the same interleave inside every head, with the two
+// halves of the head in the roles of gate and up: tile 4*head + t, row n holds the head's dim
+// 16t + 8(j/2) + 4h + r (j even) or that dim + 64 (j odd), so that a lane owns both members of a
+// rotary pair (i, i + 64).
 // ---------------------------------------------------------------------------
 __global__ void pack_bf16_kernel(uint4 *dst, const uint16_t *src, int K, int64_t n_chunks, int mode, int tile_add) {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -97,6 +101,10 @@ __global__ void pack_bf16_kernel(uint4 *dst, const uint16_t *src, int K, int64_t
     int64_t row;
     if (mode == 0) {
         row = (t - tile_add) * 32 + n;
+    } else if (mode == 3) {
+        const int j = n >> 3;
+        const int64_t tt = t - tile_add;
+        row = (tt >> 2) * 128 + (j & 1) * 64 + (tt & 3) * 16 + 8 * (j >> 1) + (n & 7);
     } else {
         const int j = n >> 3;
         if ((j & 1) != mode - 1) return;             // this launch fills only its own 4-row groups
@@ -105,21 +113,32 @@ __global__ void pack_bf16_kernel(uint4 *dst, const uint16_t *src, int K, int64_t
     dst[(t * ksteps + kt) * 64 + lane] = *(const uint4 *)(src + row * K + k);
 }
 
-// n_rows source rows.  mode 0: destination tiles tile_add .. tile_add + n_rows/32 - 1;
+// n_rows source rows.  modes 0, 3: destination tiles tile_add .. tile_add + n_rows/32 - 1;
 // modes 1, 2: destination tiles 0 .. n_rows/16 - 1.
 void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int mode, int tile_add, hipStream_t st) {
-    const int64_t tiles = mode == 0 ? n_rows / 32 : n_rows / 16;
+    const bool whole = mode == 0 || mode == 3;
+    const int64_t tiles = whole ? n_rows / 32 : n_rows / 16;
     const int64_t n_chunks = tiles * (K / 16) * 64;
-    uint4 *d = (uint4 *)dst + (mode == 0 ? (int64_t)tile_add * (K / 16) * 64 : 0);
+    uint4 *d = (uint4 *)dst + (whole ? (int64_t)tile_add * (K / 16) * 64 : 0);
     hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)((n_chunks + 255) / 256)), dim3(256), 0, st, d, src, K, n_chunks,
                        mode, 0);
 }
 
 // ---------------------------------------------------------------------------
-// embedding gather + first RMSNorm.  One block per row.
+// embedding gather.  One block per row: h = E[token] (float32), xa = split(h * g) for the first
+// QKV GEMM (which applies the row's RMS scale in its epilogue), ssq = fixed-point sum of squares.
 // ---------------------------------------------------------------------------
+// Sums of squares of the residual rows are accumulated by many blocks; they are kept as 64-bit
+// fixed point (2^-30 units) so that the atomic additions commute and the result is reproducible.
+#define SSQ_SCALE 1073741824.0f
+__device__ __forceinline__ unsigned long long ssq_fix(float v) { return (unsigned long long)(fminf(v, 8.0e9f) * SSQ_SCALE); }
+__device__ __forceinline__ float rms_scale(unsigned long long q, float inv_d, float eps) {
+    return 1.0f / sqrtf((float)((double)q * (1.0 / 1073741824.0)) * inv_d + eps);
+}
+
 __global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, const int32_t *row_tok, const float *g,
-                                                         float *h, uint16_t *xa, int d, int m_tiles, float eps) {
+                                                         float *h, uint16_t *xa, unsigned long long *ssq_out,
+                                                         unsigned long long *ssq_clear, int d, int m_tiles) {
     __shared__ float red[4];
     const int m = blockIdx.x;
     const uint16_t *src = E + (size_t)row_tok[m] * d;
@@ -138,80 +157,283 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, cons
         for (int i = 0; i < 8; ++i) ss += v[i] * v[i];
         *(float4 *)(hr + c * 8) = make_float4(v[0], v[1], v[2], v[3]);
         *(float4 *)(hr + c * 8 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] *= g[c * 8 + i];
+        store_split8(xa, m, c * 8, m_tiles, v);
     }
     ss = block_sum<256>(ss, red);
-    const float r = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = threadIdx.x; c < d / 8; c += 256) {
-        float v[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = hr[c * 8 + i] * r * g[c * 8 + i];
-        store_split8(xa, m, c * 8, m_tiles, v);
+    if (threadIdx.x == 0) {
+        ssq_out[m] = ssq_fix(ss);
+        ssq_clear[m] = 0ull;
     }
 }
 
 // ---------------------------------------------------------------------------
-// residual add of split-K partial sums + RMSNorm of the updated stream.  One block per row.
-//   h[m] += sum_s part[s][m]   (fixed order)        xa = split(rmsnorm(h[m]) * g)
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void resid_norm_kernel(float *h, const float *part, int S, int M, const float *g,
-                                                          uint16_t *xa, int d, int m_tiles, float eps) {
-    __shared__ float red[16];
-    const int m = blockIdx.x;
-    float *hr = h + (size_t)m * d;
-    float ss = 0.f;
-    for (int c = threadIdx.x; c < d / 4; c += 1024) {
-        float4 a = *(float4 *)(hr + c * 4);
-        for (int s = 0; s < S; ++s) {
-            const float4 p = *(const float4 *)(part + ((size_t)s * M + m) * d + c * 4);
-            a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
-        }
-        *(float4 *)(hr + c * 4) = a;
-        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
-    }
-    ss = block_sum<1024>(ss, red);      // also orders the writes of h before the reads below
-    const float r = 1.0f / sqrtf(ss / (float)d + eps);
-    for (int c = threadIdx.x; c < d / 8; c += 1024) {
-        float v[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = hr[c * 8 + i] * r * g[c * 8 + i];
-        store_split8(xa, m, c * 8, m_tiles, v);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// skinny-M GEMM on the matrix cores:  Y[M][N] = X[M][K] * W[N][K]^T
+// skinny-M GEMM on the matrix cores:  Y[M][N] = X[M][K] * W[N][K]^T, with the stage that follows
+// the GEMM fused into its epilogue.
 //
 // A block of 4 waves covers up to 128 rows (MT tiles of 32) and 4*NT column tiles of 32; wave w
 // owns NT column tiles.  Weights go global -> registers, one fully coalesced 1 KiB fragment per
-// load, PF stages ahead; each weight byte is read once per 128 rows.  Activations (hi and lo
+// load, PF stages ahead; each weight byte is read once per row block.  Activations (hi and lo
 // planes, already in fragment order) go global -> LDS once per block and are shared by the 4 waves.
 // MFMA 32x32x16: A = weight tile (32 n x 16 k), B = activation tile (16 k x 32 m), so a lane ends up
-// with 4 consecutive output columns of one row per register quad (vector stores along N).
+// with 4 consecutive output columns of one row per register quad.
 // grid: 1-D over (column group, split-K slice, row block of MT tiles); see the block index decode.
+//
+// Split-K.  With S = 1 the block runs the epilogue itself.  With S > 1 it stores its accumulators
+// in register order (coalesced 1 KiB stores) and gemm_fixup_kernel, one wave per 32x32 output
+// tile, adds the S slices in slice order and runs the same epilogue code.
+//
+// Normalisation.  RMSNorm scales row m by r[m] = 1/rms(h[m]) and column k by the gain g[k].  The
+// producer of an activation matrix writes split(h * g) and the rows' sums of squares; the
+// consuming GEMM multiplies its accumulators by r[m] (the scale commutes with the contraction).
+//
+// Epilogues (per 32x32 tile):
+//   EPI_QKV    rotary embedding of q and k (weight rows of every head are interleaved so that a
+//              lane holds both members of 4 rotary pairs), q -> hi/lo planes for the attention
+//              kernel, k and v -> bf16 into the paged cache at position P + node
+//   EPI_RESID  h += Y; xout = split(h * gain); adds the tile's sums of squares to ssq_out and
+//              clears the buffer the next producer will add to
+//   EPI_SWIGLU act = split(silu(gate) * up), gate and up rows interleaved in the weight tiles
+//   EPI_ARGMAX per-wave arg-max of every row (+ optional float32 logits); never split
 // ---------------------------------------------------------------------------
-enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2 };
+enum { EPI_QKV = 0, EPI_SWIGLU = 1, EPI_ARGMAX = 2, EPI_RESID = 3 };
 
 struct GemmArgs {
     const uint4 *W;          // re-tiled weights
     const uint4 *X;          // xpack activations
     int n_tiles, k_steps, m_tiles_total, M, N;
-    int col_groups, m_blocks, splits;   // grid decomposition (see the kernel's block index decode)
-    float *part;             // EPI_PARTIAL: [S][M][N]
-    uint16_t *act;           // EPI_SWIGLU: xpack with K = N/2 (N counts gate and up rows)
-    float *lm_val;           // EPI_ARGMAX: [gridDim.x*4][lm_stride]
+    int col_groups, m_blocks, splits, mt, nt;   // grid decomposition (see the kernel's block index decode)
+    float *part;             // split-K exchange: [S][col group][row block][wave][NT][MT][4][64] float4
+    const unsigned long long *ssq_in;   // [rows] sums of squares of the input rows, or null (input is not a normed stream)
+    float inv_d, eps;
+    // EPI_RESID
+    float *h;                // residual stream [M][N]
+    const float *gain;       // gains of the norm that follows
+    uint16_t *xout;          // xpack (K = N) of h * gain
+    unsigned long long *ssq_out, *ssq_clear;   // [rows]
+    // EPI_SWIGLU
+    uint16_t *act;           // xpack with K = N/2 (N counts gate and up rows)
+    // EPI_QKV
+    const float2 *row_cs;    // [rows][64] (cos, sin)
+    const int32_t *row_kvloc; // [rows] physical page * 16 + token in page of the row's cache position
+    int Hq, Hkv;
+    char *k_layer;           // K pages of this layer; V pages follow at v_offset
+    size_t v_offset;
+    uint16_t *q_planes;      // [2][M][Hq*128]
+    // EPI_ARGMAX
+    float *lm_val;           // [col groups * 4][lm_stride]
     int32_t *lm_idx;
     int lm_stride;
-    float *logits;           // EPI_ARGMAX, optional: [M][N]
+    float *logits;           // optional: [M][N]
 };
+
+// Epilogue of one 32x32 output tile held in MFMA register order: lane (row = lane % 32, h = lane / 32)
+// owns columns 8j + 4h + r (j = 0..3, r = 0..3) in acc[4j + r].  T = column tile, m = the lane's row.
+// tile_pre issues every load the epilogue needs that does not depend on the accumulators (so that a
+// caller can overlap them with its own loads); tile_epilogue consumes them and returns the lane's
+// share of the tile's sum of squares (EPI_RESID).
+struct TilePre {
+    float rs;                // RMS scale of the row
+    float4 hv[4], gn[4];     // EPI_RESID: residual values and gains of the lane's 16 columns
+    float4 cs[4];            // EPI_QKV: (cos, sin) of the lane's 8 rotary pairs
+    int kvloc;               // EPI_QKV: physical page * 16 + token in page of the row's cache position
+};
+
+template <int EPI>
+__device__ __forceinline__ TilePre tile_pre(const GemmArgs &g, int T, int m, int nsub) {
+    TilePre p;
+    p.rs = 1.0f;
+    p.kvloc = 0;
+    if (m >= g.M) return p;
+    if (g.ssq_in) p.rs = rms_scale(g.ssq_in[m], g.inv_d, g.eps);
+    if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int nn = T * 32 + 8 * j + nsub;
+            p.hv[j] = *(const float4 *)(g.h + (size_t)m * g.N + nn);
+            p.gn[j] = *(const float4 *)(g.gain + nn);
+        }
+    } else if constexpr (EPI == EPI_QKV) {
+        const int hy = T >> 2, th = T & 3;
+        if (hy >= g.Hq) p.kvloc = g.row_kvloc[m];
+        if (hy < g.Hq + g.Hkv) {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int i0 = 16 * th + 8 * jj + nsub;
+                p.cs[2 * jj] = *(const float4 *)(g.row_cs + (size_t)m * 64 + i0);
+                p.cs[2 * jj + 1] = *(const float4 *)(g.row_cs + (size_t)m * 64 + i0 + 2);
+            }
+        }
+    }
+    return p;
+}
+
+template <int EPI>
+__device__ __forceinline__ float tile_epilogue(const GemmArgs &g, const f32x16 &acc, int T, int m, int nsub, const TilePre &p) {
+    float ss = 0.f;
+    if (m >= g.M) return ss;
+    const float rs = p.rs;
+    if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int nn = T * 32 + 8 * j + nsub;
+            float4 v = p.hv[j];
+            v.x += acc[4 * j]; v.y += acc[4 * j + 1]; v.z += acc[4 * j + 2]; v.w += acc[4 * j + 3];
+            *(float4 *)(g.h + (size_t)m * g.N + nn) = v;
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            const float4 gn = p.gn[j];
+            uint32_t hi[2], lo[2];
+            split_pack2(v.x * gn.x, v.y * gn.y, hi[0], lo[0]);
+            split_pack2(v.z * gn.z, v.w * gn.w, hi[1], lo[1]);
+            *(uint2 *)(g.xout + xpack_index(m, nn, 0, g.m_tiles_total)) = make_uint2(hi[0], hi[1]);
+            *(uint2 *)(g.xout + xpack_index(m, nn, 1, g.m_tiles_total)) = make_uint2(lo[0], lo[1]);
+        }
+    } else if constexpr (EPI == EPI_SWIGLU) {
+        // the tile holds gate (register groups j = 0, 2) and up (j = 1, 3) of 16 feed-forward columns
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            float v[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float gt = acc[8 * jj + r] * rs, up = acc[8 * jj + 4 + r] * rs;
+                v[r] = gt / (1.0f + __expf(-gt)) * up;
+            }
+            uint32_t hi[2], lo[2];
+            split_pack2(v[0], v[1], hi[0], lo[0]);
+            split_pack2(v[2], v[3], hi[1], lo[1]);
+            const int f0 = T * 16 + 8 * jj + nsub;
+            *(uint2 *)(g.act + xpack_index(m, f0, 0, g.m_tiles_total)) = make_uint2(hi[0], hi[1]);
+            *(uint2 *)(g.act + xpack_index(m, f0, 1, g.m_tiles_total)) = make_uint2(lo[0], lo[1]);
+        }
+    } else if constexpr (EPI == EPI_QKV) {
+        // tile T = 4 * head + t: register groups j = 0, 2 hold dims 16t + 8(j/2) + 4h + r of the head,
+        // groups j = 1, 3 the same dims + 64 (the rotary partners)
+        const size_t qd = (size_t)g.Hq * 128;
+        const int hy = T >> 2, th = T & 3;
+        uint16_t *kc = nullptr, *vc = nullptr;
+        int tk = 0;
+        if (hy >= g.Hq) {
+            const int kvh = hy < g.Hq + g.Hkv ? hy - g.Hq : hy - g.Hq - g.Hkv;
+            const size_t pb = ((size_t)(p.kvloc >> 4) * g.Hkv + kvh) * (SEV_PAGE * 128);
+            kc = (uint16_t *)g.k_layer + pb;
+            vc = (uint16_t *)(g.k_layer + g.v_offset) + pb;
+            tk = p.kvloc & 15;
+        }
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int i0 = 16 * th + 8 * jj + nsub;
+            float va[4], vb[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                va[r] = acc[8 * jj + r] * rs;
+                vb[r] = acc[8 * jj + 4 + r] * rs;
+            }
+            if (hy < g.Hq + g.Hkv) {
+                const float4 c01 = p.cs[2 * jj], c23 = p.cs[2 * jj + 1];
+                const float cs[4] = {c01.x, c01.z, c23.x, c23.z}, sn[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float x = va[r], y = vb[r];
+                    va[r] = x * cs[r] - y * sn[r];
+                    vb[r] = y * cs[r] + x * sn[r];
+                }
+            }
+            if (hy < g.Hq) {
+                uint32_t hi[2], lo[2];
+                const size_t o = (size_t)m * qd + (size_t)hy * 128 + i0;
+                split_pack2(va[0], va[1], hi[0], lo[0]);
+                split_pack2(va[2], va[3], hi[1], lo[1]);
+                *(uint2 *)(g.q_planes + o) = make_uint2(hi[0], hi[1]);
+                *(uint2 *)(g.q_planes + (size_t)g.M * qd + o) = make_uint2(lo[0], lo[1]);
+                split_pack2(vb[0], vb[1], hi[0], lo[0]);
+                split_pack2(vb[2], vb[3], hi[1], lo[1]);
+                *(uint2 *)(g.q_planes + o + 64) = make_uint2(hi[0], hi[1]);
+                *(uint2 *)(g.q_planes + (size_t)g.M * qd + o + 64) = make_uint2(lo[0], lo[1]);
+            } else if (hy < g.Hq + g.Hkv) {
+                *(uint2 *)(kc + k_in_page<true>(tk, i0, 128)) =
+                    make_uint2(f32_to_bf16_bits(va[0]) | (f32_to_bf16_bits(va[1]) << 16),
+                               f32_to_bf16_bits(va[2]) | (f32_to_bf16_bits(va[3]) << 16));
+                *(uint2 *)(kc + k_in_page<true>(tk, i0 + 64, 128)) =
+                    make_uint2(f32_to_bf16_bits(vb[0]) | (f32_to_bf16_bits(vb[1]) << 16),
+                               f32_to_bf16_bits(vb[2]) | (f32_to_bf16_bits(vb[3]) << 16));
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    vc[v_in_page<true>(tk, i0 + r, 128)] = (uint16_t)f32_to_bf16_bits(va[r]);
+                    vc[v_in_page<true>(tk, i0 + 64 + r, 128)] = (uint16_t)f32_to_bf16_bits(vb[r]);
+                }
+            }
+        }
+    }
+    return ss;
+}
+
+// Adds a block's per-row sums of squares (one value per lane < 32 and wave, in red[wave][row]) to
+// ssq_out and clears ssq_clear; rows = number of rows covered, m0 = first row.
+__device__ __forceinline__ void ssq_commit(const GemmArgs &g, float (*red)[128], int rows, int m0, bool clear) {
+    __syncthreads();
+    if ((int)threadIdx.x < rows) {
+        const int t = threadIdx.x, m = m0 + t;
+        if (m < g.M) {
+            atomicAdd(g.ssq_out + m, ssq_fix((red[0][t] + red[1][t]) + (red[2][t] + red[3][t])));
+            if (clear) g.ssq_clear[m] = 0ull;
+        }
+    }
+}
+
+#ifdef SEV_TRACE
+// timing probes for tuning experiments (never compiled into the library proper)
+__device__ unsigned long long *g_trace;
+__device__ unsigned g_trace_pos, g_trace_cap;
+#define SEV_TRACE_T(var) const unsigned long long var = wall_clock64()
+extern "C" int sev_trace_begin(int cap) {
+    unsigned long long *buf;
+    if (hipMalloc(&buf, (size_t)cap * 64) != hipSuccess) return -1;
+    unsigned zero = 0, c = (unsigned)cap;
+    hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &buf, sizeof(buf));
+    hipMemcpyToSymbol(HIP_SYMBOL(g_trace_pos), &zero, 4);
+    hipMemcpyToSymbol(HIP_SYMBOL(g_trace_cap), &c, 4);
+    return 0;
+}
+extern "C" int sev_trace_read(unsigned long long *host, int cap) {
+    unsigned long long *buf; unsigned n;
+    hipDeviceSynchronize();
+    hipMemcpyFromSymbol(&buf, HIP_SYMBOL(g_trace), sizeof(buf));
+    hipMemcpyFromSymbol(&n, HIP_SYMBOL(g_trace_pos), 4);
+    if ((int)n > cap) n = cap;
+    hipMemcpy(host, buf, (size_t)n * 64, hipMemcpyDeviceToHost);
+    unsigned zero = 0;
+    hipMemcpyToSymbol(HIP_SYMBOL(g_trace_pos), &zero, 4);
+    return (int)n;
+}
+#define SEV_TRACE_END(t4)                                                                                              \
+    if (threadIdx.x == 0 && g_trace) {                                                                                 \
+        SEV_TRACE_T(tr_e);                                                                                             \
+        const unsigned i_ = atomicAdd(&g_trace_pos, 1u);                                                               \
+        if (i_ < g_trace_cap) {                                                                                        \
+            unsigned long long *t_ = g_trace + (size_t)i_ * 8;                                                         \
+            t_[0] = (unsigned long long)EPI | ((unsigned long long)g.N << 8) | ((unsigned long long)g.splits << 40);   \
+            t_[1] = blockIdx.x | ((unsigned long long)(t4) << 32);                                                     \
+            t_[2] = (unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11));                                    \
+            t_[3] = tr0; t_[4] = tr1; t_[5] = tr2; t_[6] = tr_e; t_[7] = n;                                            \
+        }                                                                                                              \
+    }
+#else
+#define SEV_TRACE_T(var)
+#define SEV_TRACE_END(t4)
+#endif
 
 template <int MT, int NT, int EPI, int PF>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     extern __shared__ u32x4 xs[];                       // [2 buffers][2 k-steps][MT][2 planes][64 lanes]
+    __shared__ float red[4][128];
+    SEV_TRACE_T(tr0);
     constexpr int STAGE_U4 = 2 * MT * 2 * 64;           // uint4 per stage
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // Block index decode, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, each with its
-    // own L2.  Blocks that re-read the same weight tiles (the row blocks of one column group) get ids 8
-    // apart, i.e. land on the same XCD back to back, so the second read hits that L2.
+    // own L2.  Blocks that share weight tiles (the row blocks of one column group) get ids 8 apart,
+    // i.e. land on the same XCD back to back, so the second read can hit that L2.
     int q = blockIdx.x >> 3;
     const int mb = q % g.m_blocks;
     q /= g.m_blocks;
@@ -224,6 +446,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const int s_begin = (int)((int64_t)n_stages * split / g.splits);
     const int s_end = (int)((int64_t)n_stages * (split + 1) / g.splits);
     const int n = s_end - s_begin;
+    const int mrow = lane & 31, nsub = 4 * (lane >> 5);
 
     f32x16 acc[NT][MT];
 #pragma unroll
@@ -251,6 +474,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // The loop body is PF stages of straight-line code (no branches), which lets the compiler's
     // wait-count bookkeeping follow the loads across the back-edge.  The slice is padded to a multiple
     // of PF stages: padded stages re-load the last stage (cached) and feed zero activations.
+    // Weights are read exactly once per row block: their loads carry the streaming (non-temporal) hint.
     static_assert(PF % 2 == 0, "LDS buffer parity must follow the slot index");
     u32x4 wreg[PF][NT][2];
     u32x4 xreg[PF][MT];
@@ -263,7 +487,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         xsrc[i] = (const u32x4 *)g.X + ((size_t)ksl * g.m_tiles_total + mt0) * 128 + within;
     }
     const size_t x_stage = (size_t)2 * g.m_tiles_total * 128;      // 16-byte units per stage of all row tiles
-    const int s_last = s_end - 1;
+    const int s_last_stage = s_end - 1;
     const int n_pad = (n + PF - 1) / PF * PF;
     const u32x4 zero4 = (u32x4){0u, 0u, 0u, 0u};
 
@@ -272,17 +496,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
             x0[i] = xsrc[i][(size_t)s_begin * x_stage];
-            x1[i] = xsrc[i][(size_t)min(s_begin + 1, s_last) * x_stage];
+            x1[i] = xsrc[i][(size_t)min(s_begin + 1, s_last_stage) * x_stage];
         }
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
-            const int sx = min(s_begin + u + 2, s_last), sw = min(s_begin + u, s_last);
+            const int sx = min(s_begin + u + 2, s_last_stage), sw = min(s_begin + u, s_last_stage);
 #pragma unroll
             for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
 #pragma unroll
             for (int a = 0; a < NT; ++a)
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = wp[a][(size_t)(2 * sw + ks) * 64];
+                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(2 * sw + ks) * 64]);
         }
 #pragma unroll
         for (int i = 0; i < MT; ++i) {
@@ -291,6 +515,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         }
     }
     __syncthreads();
+    SEV_TRACE_T(tr1);
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -331,68 +556,66 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             for (int i = 0; i < MT; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
             __builtin_amdgcn_sched_barrier(0);
             // refill this slot: activations first, then weights (the order they will be waited on)
-            const int sx = min(s_begin + st + PF + 2, s_last), sw = min(s_begin + st + PF, s_last);
+            const int sx = min(s_begin + st + PF + 2, s_last_stage), sw = min(s_begin + st + PF, s_last_stage);
 #pragma unroll
             for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
 #pragma unroll
             for (int a = 0; a < NT; ++a)
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = wp[a][(size_t)(2 * sw + ks) * 64];
+                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(2 * sw + ks) * 64]);
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
         }
     }
+    SEV_TRACE_T(tr2);
+
+    // ------------------------------------------------------------------ split-K: hand the slice to the fix-up kernel
+    if (g.splits > 1) {
+        const size_t per_block = (size_t)4 * NT * MT * 4 * 64;          // float4 per block
+        const size_t blk = (size_t)cg * g.m_blocks + mb;
+        float4 *mine = (float4 *)g.part + ((size_t)split * g.col_groups * g.m_blocks + blk) * per_block +
+                       (size_t)wave * (NT * MT * 4 * 64) + lane;
+#pragma unroll
+        for (int a = 0; a < NT; ++a)
+#pragma unroll
+            for (int b = 0; b < MT; ++b)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    mine[((a * MT + b) * 4 + j) * 64] =
+                        make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+        SEV_TRACE_END(0);
+        return;
+    }
 
     // ------------------------------------------------------------------ epilogues
-    const int mrow = lane & 31, nsub = 4 * (lane >> 5);
-    if constexpr (EPI == EPI_PARTIAL) {
-        float *out = g.part + (size_t)split * g.M * g.N;
+    if constexpr (EPI != EPI_ARGMAX) {
+        float ss[MT];
 #pragma unroll
-        for (int a = 0; a < NT; ++a) {
-            if (tile0 + a >= g.n_tiles) continue;
+        for (int b = 0; b < MT; ++b) {
+            ss[b] = 0.f;
+            const int m = (mt0 + b) * 32 + mrow;
 #pragma unroll
-            for (int b = 0; b < MT; ++b) {
-                const int m = (mt0 + b) * 32 + mrow;
-                if (m >= g.M) continue;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int nn = (tile0 + a) * 32 + 8 * j + nsub;
-                    *(float4 *)(out + (size_t)m * g.N + nn) =
-                        make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+            for (int a = 0; a < NT; ++a)
+                if (tile0 + a < g.n_tiles) {
+                    const TilePre pre = tile_pre<EPI>(g, tile0 + a, m, nsub);
+                    ss[b] += tile_epilogue<EPI>(g, acc[a][b], tile0 + a, m, nsub, pre);
                 }
-            }
         }
-    } else if constexpr (EPI == EPI_SWIGLU) {
-        // each 32-row weight tile holds gate (register groups j = 0, 2) and up (j = 1, 3) of 16 columns
-#pragma unroll
-        for (int a = 0; a < NT; ++a) {
-            if (tile0 + a >= g.n_tiles) continue;
+        if constexpr (EPI == EPI_RESID) {
 #pragma unroll
             for (int b = 0; b < MT; ++b) {
-                const int m = (mt0 + b) * 32 + mrow;
-                if (m >= g.M) continue;
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    float v[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float gt = acc[a][b][8 * jj + r], up = acc[a][b][8 * jj + 4 + r];
-                        v[r] = gt / (1.0f + __expf(-gt)) * up;
-                    }
-                    uint32_t hi[2], lo[2];
-                    split_pack2(v[0], v[1], hi[0], lo[0]);
-                    split_pack2(v[2], v[3], hi[1], lo[1]);
-                    const int f0 = (tile0 + a) * 16 + 8 * jj + nsub;
-                    *(uint2 *)(g.act + xpack_index(m, f0, 0, g.m_tiles_total)) = make_uint2(hi[0], hi[1]);
-                    *(uint2 *)(g.act + xpack_index(m, f0, 1, g.m_tiles_total)) = make_uint2(lo[0], lo[1]);
-                }
+                ss[b] += __shfl_xor(ss[b], 32);
+                if (lane < 32) red[wave][b * 32 + mrow] = ss[b];
             }
+            ssq_commit(g, red, MT * 32, mt0 * 32, cg == 0);
         }
     } else {
-        // arg-max over this wave's columns for every row (lowest index wins ties)
+        // arg-max over this wave's columns for every row (lowest index wins ties); the row scale is
+        // positive, so it only matters for the logits that are written out
 #pragma unroll
         for (int b = 0; b < MT; ++b) {
             const int m = (mt0 + b) * 32 + mrow;
+            const float rsb = (g.logits && g.ssq_in && m < g.M) ? rms_scale(g.ssq_in[m], g.inv_d, g.eps) : 1.0f;
             float bv = -INFINITY;
             int bi = 0x7fffffff;
 #pragma unroll
@@ -408,7 +631,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                     }
                     if (g.logits && m < g.M)
                         *(float4 *)(g.logits + (size_t)m * g.N + nn) =
-                            make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+                            make_float4(acc[a][b][4 * j] * rsb, acc[a][b][4 * j + 1] * rsb, acc[a][b][4 * j + 2] * rsb,
+                                        acc[a][b][4 * j + 3] * rsb);
                 }
             }
             const float ov = __shfl_xor(bv, 32);
@@ -421,8 +645,63 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             }
         }
     }
+    SEV_TRACE_END(1);
 }
 
+// Split-K fix-up: block (column group cg, row tile mt, a) of 4 waves; wave w sums the S slices of the
+// 32x32 tile (column tile (cg*4 + w)*NT + a, row tile mt) in slice order and runs its epilogue.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g) {
+    __shared__ float red[4][128];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int MT = g.mt, NT = g.nt;
+    int q = blockIdx.x;
+    const int a = q % NT; q /= NT;
+    const int mtn = g.m_blocks * MT;
+    const int mt = q % mtn;
+    const int cg = q / mtn;
+    const int mb = mt / MT, b = mt - mb * MT;
+    const int T = (cg * 4 + wave) * NT + a;
+    const int mrow = lane & 31, nsub = 4 * (lane >> 5);
+    const int m = mt * 32 + mrow;
+    const size_t per_block = (size_t)4 * NT * MT * 4 * 64;
+    const size_t slice_stride = (size_t)g.col_groups * g.m_blocks * per_block;
+    const float4 *src = (const float4 *)g.part + ((size_t)cg * g.m_blocks + mb) * per_block +
+                        (size_t)wave * (NT * MT * 4 * 64) + (size_t)((a * MT + b) * 4) * 64 + lane;
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const bool live = T < g.n_tiles;
+    float ss = 0.f;
+    if (live) {
+        const TilePre pre = tile_pre<EPI>(g, T, m, nsub);       // issued ahead of the slice loads
+        for (int s0 = 0; s0 < g.splits; s0 += 8) {
+            float4 v[8][4];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    v[u][j] = src[(size_t)min(s0 + u, g.splits - 1) * slice_stride + j * 64];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < g.splits) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        acc[4 * j] += v[u][j].x; acc[4 * j + 1] += v[u][j].y;
+                        acc[4 * j + 2] += v[u][j].z; acc[4 * j + 3] += v[u][j].w;
+                    }
+                }
+        }
+        ss = tile_epilogue<EPI>(g, acc, T, m, nsub, pre);
+    }
+    if constexpr (EPI == EPI_RESID) {
+        ss += __shfl_xor(ss, 32);
+        if (lane < 32) red[wave][mrow] = ss;
+        ssq_commit(g, red, 32, mt * 32, cg == 0 && a == 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // final arg-max over the per-wave partial results of the LM-head GEMM; one block per row
 __global__ __launch_bounds__(256) void lm_reduce_kernel(const float *val, const int32_t *idx, int n_part, int stride,
                                                         int32_t *out) {
@@ -451,54 +730,6 @@ __global__ __launch_bounds__(256) void lm_reduce_kernel(const float *val, const 
 }
 
 // ---------------------------------------------------------------------------
-// QKV post-processing: sum split-K partials, rotate q and k, write q as hi/lo planes for the
-// attention kernel and append k, v (bf16) to the paged cache at position P + node.
-// grid (rows, Hq + Hkv), 64 threads: thread i owns the rotary pair (i, i + 64).
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void rope_kv_bf16_kernel(const float *part, int S, int M, int n_qkv, DevPlan p, KvGeom g,
-                                                          const int32_t *page_table, int max_pages, int layer, int Hq,
-                                                          uint16_t *q_planes) {
-    const int m = blockIdx.x, hy = blockIdx.y, i = threadIdx.x;
-    const float2 cs = p.row_cs[(size_t)m * 64 + i];
-    const int col = (hy < Hq ? hy * 128 : Hq * 128 + (hy - Hq) * 128);
-    float a = 0.f, b = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float *r = part + ((size_t)s * M + m) * n_qkv + col;
-        a += r[i];
-        b += r[i + 64];
-    }
-    if (hy < Hq) {
-        const float ra = a * cs.x - b * cs.y, rb = b * cs.x + a * cs.y;
-        uint32_t h0, l0, h1, l1;
-        split_bf16(ra, h0, l0);
-        split_bf16(rb, h1, l1);
-        const size_t qd = (size_t)Hq * 128, o = (size_t)m * qd + hy * 128;
-        q_planes[o + i] = (uint16_t)h0;
-        q_planes[o + i + 64] = (uint16_t)h1;
-        q_planes[(size_t)M * qd + o + i] = (uint16_t)l0;
-        q_planes[(size_t)M * qd + o + i + 64] = (uint16_t)l1;
-        return;
-    }
-    const int h = hy - Hq, rb_ = p.row_req[m];
-    const int tok = p.req_P[rb_] + p.row_node[m], slot = p.req_slot[rb_];
-    const size_t pb = ((size_t)page_table[(size_t)slot * max_pages + tok / SEV_PAGE] * g.Hkv + h) * (SEV_PAGE * 128);
-    uint16_t *kc = (uint16_t *)(g.pool + (size_t)layer * g.layer_stride) + pb;
-    uint16_t *vc = (uint16_t *)(g.pool + (size_t)layer * g.layer_stride + g.v_offset) + pb;
-    const int t = tok % SEV_PAGE;
-    kc[k_in_page<true>(t, i, 128)] = (uint16_t)f32_to_bf16_bits(a * cs.x - b * cs.y);
-    kc[k_in_page<true>(t, i + 64, 128)] = (uint16_t)f32_to_bf16_bits(b * cs.x + a * cs.y);
-    // v columns follow the k columns of all KV heads
-    float va = 0.f, vb = 0.f;
-    for (int s = 0; s < S; ++s) {
-        const float *r = part + ((size_t)s * M + m) * n_qkv + col + g.Hkv * 128;
-        va += r[i];
-        vb += r[i + 64];
-    }
-    vc[v_in_page<true>(t, i, 128)] = (uint16_t)f32_to_bf16_bits(va);
-    vc[v_in_page<true>(t, i + 64, 128)] = (uint16_t)f32_to_bf16_bits(vb);
-}
-
-// ---------------------------------------------------------------------------
 // verification attention over the paged bf16 cache (head_dim 128, 16-token pages).
 //
 // Work item = (request, group of 32 query rows, KV chunk) x KV head.  The 32 rows are
@@ -515,6 +746,7 @@ __global__ __launch_bounds__(64) void rope_kv_bf16_kernel(const float *part, int
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g, int layer, int Hq,
                                                            float *att_o, float2 *att_ml, float scale_log2e) {
     extern __shared__ float lds[];                    // two merge slots (64 accumulator registers + max + sum per lane), then the q fragments
+    SEV_TRACE_T(tr0);
     const int item = blockIdx.x, kvh = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // everything the block needs to know comes from two 16-byte loads and one page-id load, all independent
@@ -591,6 +823,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
         load_v(0);
     }
     __syncthreads();                                       // q fragments are in LDS
+    SEV_TRACE_T(tr1);
 
     auto pair_step = [&](int i, auto prefetch_tag) {
         constexpr bool PREFETCH = decltype(prefetch_tag)::value;
@@ -674,6 +907,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
     };
     for (int i = 0; i + 1 < my_pairs; ++i) pair_step(i, std::true_type{});
     if (my_pairs > 0) pair_step(my_pairs - 1, std::false_type{});
+    SEV_TRACE_T(tr2);
 
     // ---- merge the 4 waves pairwise through LDS, in the accumulators' own register layout
     // (wave 1 -> 0 and 3 -> 2, then 2 -> 0); wave 0 writes the block's partial result.
@@ -729,6 +963,18 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
                     make_float4(oacc[t][qt][0], oacc[t][qt][1], oacc[t][qt][2], oacc[t][qt][3]);
         }
     }
+#ifdef SEV_TRACE
+    if (threadIdx.x == 0 && g_trace) {
+        SEV_TRACE_T(tr_e);
+        const unsigned i_ = atomicAdd(&g_trace_pos, 1u);
+        if (i_ < g_trace_cap) {
+            unsigned long long *t_ = g_trace + (size_t)i_ * 8;
+            t_[0] = 100; t_[1] = blockIdx.x | ((unsigned long long)blockIdx.y << 32);
+            t_[2] = (unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11));
+            t_[3] = tr0; t_[4] = tr1; t_[5] = tr2; t_[6] = tr_e; t_[7] = npages;
+        }
+    }
+#endif
 }
 
 // cross-chunk merge + normalisation; writes the attention output as hi/lo fragments for the O projection.
@@ -776,24 +1022,26 @@ enum { G_QKV = 0, G_O, G_GU, G_DOWN, G_LM };
 // Tile configuration of one GEMM.  Row tiles per block MT (weights are re-read through L2 by each row
 // block), column tiles per wave NT, split-K slices S, prefetch depth PF.  Environment variables
 // SEV_TUNE_QKV / _O / _GU / _DOWN / _LM = "MT,NT,S,PF" override the choice (tuning experiments).
-static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, int rows, size_t part_elems, int N) {
+static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size_t part_elems) {
     static const char *names[] = {"SEV_TUNE_QKV", "SEV_TUNE_O", "SEV_TUNE_GU", "SEV_TUNE_DOWN", "SEV_TUNE_LM"};
     GemmCfg c;
-    c.MT = m_tiles >= 2 ? 2 : 1;
+    c.MT = (which == G_LM && m_tiles >= 3) ? 4 : (m_tiles >= 2 ? 2 : 1);
     c.NT = (n_tiles % 2 == 0) ? 2 : 1;
     c.PF = 4;
     c.S = 1;
-    const bool splittable = which == G_QKV || which == G_O || which == G_DOWN;
+    const bool splittable = which != G_LM;
+    auto blocks_of = [&](const GemmCfg &x) {
+        return ((n_tiles + 4 * x.NT - 1) / (4 * x.NT)) * ((m_tiles + x.MT - 1) / x.MT);
+    };
     if (splittable) {
-        const int m_blocks = (m_tiles + c.MT - 1) / c.MT;
-        const int blocks = ((n_tiles + 4 * c.NT - 1) / (4 * c.NT)) * m_blocks;
-        c.S = std::min(8, std::max(1, (256 + blocks - 1) / blocks));
-        c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));
+        const int blocks = blocks_of(c);
+        c.S = std::min(16, std::max(1, 256 / blocks));
+        c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));          // at least 8 stages per slice
     }
     if (const char *e = getenv(names[which])) {
         int mt, nt, sp, pf;
         if (sscanf(e, "%d,%d,%d,%d", &mt, &nt, &sp, &pf) == 4 && (mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2) &&
-            sp >= 1 && sp <= 16 && (pf == 4 || (pf == 6 && mt <= 2))) {
+            sp >= 1 && sp <= 32 && (pf == 4 || (pf == 6 && mt <= 2))) {
             c.MT = std::min(mt, m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1));
             c.NT = nt;
             c.PF = pf;
@@ -802,7 +1050,9 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, int 
     }
     if (!splittable) c.S = 1;
     c.S = std::min(c.S, std::max(1, k_steps / 2));
-    while (c.S > 1 && (size_t)c.S * rows * N > part_elems) --c.S;
+    // the exchange buffer holds S slices of (padded columns) x (padded rows)
+    const size_t slice = (size_t)blocks_of(c) * 4 * c.NT * c.MT * 1024;
+    while (c.S > 1 && (size_t)c.S * slice > part_elems) --c.S;
     return c;
 }
 
@@ -811,6 +1061,8 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     ga.col_groups = (ga.n_tiles + 4 * c.NT - 1) / (4 * c.NT);
     ga.m_blocks = (m_tiles + c.MT - 1) / c.MT;
     ga.splits = c.S;
+    ga.mt = c.MT;
+    ga.nt = c.NT;
     const int g8 = (ga.col_groups + 7) / 8 * 8;
     dim3 grid((unsigned)(g8 * ga.m_blocks * ga.splits));
     const size_t lds = (size_t)2 * 2 * c.MT * 2 * 64 * 16;
@@ -825,6 +1077,11 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     else { if (c.PF == 6) SEV_BY_NT(1, 6); else SEV_BY_NT(1, 4); }
 #undef SEV_BY_NT
 #undef SEV_LAUNCH
+    if constexpr (EPI != EPI_ARGMAX) {
+        if (c.S > 1)
+            hipLaunchKernelGGL((gemm_fixup_kernel<EPI>), dim3((unsigned)(ga.col_groups * ga.m_blocks * c.MT * c.NT)), dim3(256), 0,
+                               st, ga);
+    }
 }
 
 void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, float *logits_out,
@@ -842,29 +1099,31 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
     {
         Prof p(kv, st, PROF_OTHER);
         hipLaunchKernelGGL(embed_norm_kernel, dim3(rows), dim3(256), 0, st, (const uint16_t *)(m->arena + m->off_embed),
-                           kv->plan.row_tok, Gp(m->layers[0].g_attn), kv->h, xa, d.d_model, m_tiles, d.rms_eps);
+                           kv->plan.row_tok, Gp(m->layers[0].g_attn), kv->h, xa, kv->ssq[1], kv->ssq[0], d.d_model, m_tiles);
     }
-    const GemmCfg pq = choose_cfg(G_QKV, m_tiles_real, m->n_qkv / 32, d.d_model / 16, rows, kv->part_elems, m->n_qkv);
-    const GemmCfg po = choose_cfg(G_O, m_tiles_real, d.d_model / 32, m->q_dim / 16, rows, kv->part_elems, d.d_model);
-    const GemmCfg pg = choose_cfg(G_GU, m_tiles_real, d.d_ffn / 16, d.d_model / 16, rows, kv->part_elems, 2 * d.d_ffn);
-    const GemmCfg pd = choose_cfg(G_DOWN, m_tiles_real, d.d_model / 32, d.d_ffn / 16, rows, kv->part_elems, d.d_model);
-    const GemmCfg pl = choose_cfg(G_LM, m_tiles_real, d.vocab / 32, d.d_model / 16, rows, kv->part_elems, d.vocab);
+    const GemmCfg pq = choose_cfg(G_QKV, m_tiles_real, m->n_qkv / 32, d.d_model / 16, kv->part_elems);
+    const GemmCfg po = choose_cfg(G_O, m_tiles_real, d.d_model / 32, m->q_dim / 16, kv->part_elems);
+    const GemmCfg pg = choose_cfg(G_GU, m_tiles_real, d.d_ffn / 16, d.d_model / 16, kv->part_elems);
+    const GemmCfg pd = choose_cfg(G_DOWN, m_tiles_real, d.d_model / 32, d.d_ffn / 16, kv->part_elems);
+    const GemmCfg pl = choose_cfg(G_LM, m_tiles_real, d.vocab / 32, d.d_model / 16, kv->part_elems);
+    GemmArgs base;
+    memset(&base, 0, sizeof(base));
+    base.m_tiles_total = m_tiles;
+    base.M = rows;
+    base.part = kv->part;
+    base.inv_d = 1.0f / (float)d.d_model;
+    base.eps = d.rms_eps;
+    base.h = kv->h;
     for (int l = 0; l < d.n_layers; ++l) {
         const LayerOffsets &lo = m->layers[l];
-        GemmArgs ga;
-        memset(&ga, 0, sizeof(ga));
-        ga.m_tiles_total = m_tiles;
-        ga.M = rows;
-        {   // QKV projection -> split-K partials
+        {   // QKV projection; rotary embedding, q planes and the cache append in its epilogue
             Prof p(kv, st, PROF_GEMM_QKV);
+            GemmArgs ga = base;
             ga.W = Wp(lo.wqkv); ga.X = (const uint4 *)xa; ga.n_tiles = m->n_qkv / 32; ga.k_steps = d.d_model / 16;
-            ga.N = m->n_qkv; ga.part = kv->part;
-            launch_gemm<EPI_PARTIAL>(ga, pq, m_tiles_real, st);
-        }
-        {
-            Prof p(kv, st, PROF_OTHER);
-            hipLaunchKernelGGL(rope_kv_bf16_kernel, dim3(rows, d.n_q_heads + d.n_kv_heads), dim3(64), 0, st, kv->part, pq.S,
-                               rows, m->n_qkv, kv->plan, g, kv->page_table, kv->max_pages_per_req, l, d.n_q_heads, qp);
+            ga.N = m->n_qkv; ga.ssq_in = kv->ssq[1];
+            ga.row_cs = kv->plan.row_cs; ga.row_kvloc = kv->plan.row_kvloc; ga.Hq = d.n_q_heads; ga.Hkv = d.n_kv_heads;
+            ga.k_layer = g.pool + (size_t)l * g.layer_stride; ga.v_offset = g.v_offset; ga.q_planes = qp;
+            launch_gemm<EPI_QKV>(ga, pq, m_tiles_real, st);
         }
         {
             Prof p(kv, st, PROF_ATTN);
@@ -874,42 +1133,34 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
                                kv->plan, d.n_q_heads, d.n_kv_heads, op, m_tiles);
         }
-        {   // output projection -> partials; residual + FFN norm
+        {   // output projection; residual add, FFN-norm operand and scale in its epilogue
             Prof p(kv, st, PROF_GEMM_O);
+            GemmArgs ga = base;
             ga.W = Wp(lo.wo); ga.X = (const uint4 *)op; ga.n_tiles = d.d_model / 32; ga.k_steps = m->q_dim / 16;
-            ga.N = d.d_model; ga.part = kv->part;
-            launch_gemm<EPI_PARTIAL>(ga, po, m_tiles_real, st);
-        }
-        {
-            Prof p(kv, st, PROF_OTHER);
-            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(1024), 0, st, kv->h, kv->part, po.S, rows, Gp(lo.g_ffn), xa,
-                               d.d_model, m_tiles, d.rms_eps);
+            ga.N = d.d_model; ga.gain = Gp(lo.g_ffn); ga.xout = xa; ga.ssq_out = kv->ssq[0]; ga.ssq_clear = kv->ssq[1];
+            launch_gemm<EPI_RESID>(ga, po, m_tiles_real, st);
         }
         {   // gate/up projection with fused SwiGLU
             Prof p(kv, st, PROF_GEMM_GU);
+            GemmArgs ga = base;
             ga.W = Wp(lo.wgu); ga.X = (const uint4 *)xa; ga.n_tiles = d.d_ffn / 16; ga.k_steps = d.d_model / 16;
-            ga.N = 2 * d.d_ffn; ga.act = act;
+            ga.N = 2 * d.d_ffn; ga.act = act; ga.ssq_in = kv->ssq[0];
             launch_gemm<EPI_SWIGLU>(ga, pg, m_tiles_real, st);
         }
-        {   // down projection -> partials; residual + next norm
+        {   // down projection; residual add, next norm's operand and scale in its epilogue
             Prof p(kv, st, PROF_GEMM_DOWN);
+            GemmArgs ga = base;
             ga.W = Wp(lo.wd); ga.X = (const uint4 *)act; ga.n_tiles = d.d_model / 32; ga.k_steps = d.d_ffn / 16;
-            ga.N = d.d_model; ga.part = kv->part;
-            launch_gemm<EPI_PARTIAL>(ga, pd, m_tiles_real, st);
-        }
-        {
-            Prof p(kv, st, PROF_OTHER);
-            const float *gn = (l + 1 < d.n_layers) ? Gp(m->layers[l + 1].g_attn) : Gp(m->off_gfinal);
-            hipLaunchKernelGGL(resid_norm_kernel, dim3(rows), dim3(1024), 0, st, kv->h, kv->part, pd.S, rows, gn, xa, d.d_model,
-                               m_tiles, d.rms_eps);
+            ga.N = d.d_model; ga.gain = (l + 1 < d.n_layers) ? Gp(m->layers[l + 1].g_attn) : Gp(m->off_gfinal); ga.xout = xa;
+            ga.ssq_out = kv->ssq[1]; ga.ssq_clear = kv->ssq[0];
+            launch_gemm<EPI_RESID>(ga, pd, m_tiles_real, st);
         }
     }
     {   // LM head with fused arg-max
         Prof p(kv, st, PROF_GEMM_LM);
-        GemmArgs ga;
-        memset(&ga, 0, sizeof(ga));
-        ga.m_tiles_total = m_tiles; ga.M = rows;
+        GemmArgs ga = base;
         ga.W = Wp(m->off_lm); ga.X = (const uint4 *)xa; ga.n_tiles = d.vocab / 32; ga.k_steps = d.d_model / 16; ga.N = d.vocab;
+        ga.ssq_in = kv->ssq[1];
         ga.lm_val = kv->lm_val; ga.lm_idx = kv->lm_idx; ga.lm_stride = m_tiles * 32; ga.logits = logits_out;
         launch_gemm<EPI_ARGMAX>(ga, pl, m_tiles_real, st);
         const int n_part = ((ga.n_tiles + 4 * pl.NT - 1) / (4 * pl.NT)) * 4;

@@ -99,6 +99,7 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
             d.p.row_pos[row0 + i] = P + depth;
             d.p.row_anc[row0 + i] = anc;
             d.p.row_tok[row0 + i] = tok;
+            d.p.row_kvloc[row0 + i] = d.page_table[(size_t)slot * d.max_pages + (P + i) / SEV_PAGE] * SEV_PAGE + (P + i) % SEV_PAGE;
             anc_prev = anc;
             depth_prev = depth;
         }

@@ -147,9 +147,10 @@ extern "C" int sev_model_load_tensor(sev_model *m, int kind, int layer, const vo
     switch (kind) {
     case SEV_W_EMBED: off = m->off_embed; rows = d.vocab; K = d.d_model; break;
     case SEV_W_LM_HEAD: off = m->off_lm; rows = d.vocab; K = d.d_model; break;
-    case SEV_W_WQ: off = lo->wqkv; rows = m->q_dim; K = d.d_model; break;
-    case SEV_W_WK: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim; break;
-    case SEV_W_WV: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim + m->kv_dim; break;
+    // q, k, v rows: rotary partners interleaved inside each head's tiles of the bf16 layout
+    case SEV_W_WQ: off = lo->wqkv; rows = m->q_dim; K = d.d_model; mode = 3; break;
+    case SEV_W_WK: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim; mode = 3; break;
+    case SEV_W_WV: off = lo->wqkv; rows = m->kv_dim; K = d.d_model; row0 = m->q_dim + m->kv_dim; mode = 3; break;
     case SEV_W_WO: off = lo->wo; rows = d.d_model; K = m->q_dim; break;
     // gate and up rows are interleaved in 4-row groups inside each 32-row tile of the bf16 layout
     case SEV_W_WG: off = lo->wgu; rows = d.d_ffn; K = d.d_model; mode = 1; break;
@@ -165,7 +166,7 @@ extern "C" int sev_model_load_tensor(sev_model *m, int kind, int layer, const vo
         // bf16 matrices are re-tiled into 32x16 MFMA operand fragments; a row offset inside a fused
         // matrix is a tile offset (all offsets are multiples of 32 by construction of the shapes)
         if (rows % 32 || row0 % 32 || K % 16) return sev_fail(SEV_EINVAL, "tensor %d: rows/K not tileable", kind);
-        launch_pack_bf16((uint16_t *)(m->arena + off), (const uint16_t *)src, rows, K, mode, mode == 0 ? row0 / 32 : 0, st);
+        launch_pack_bf16((uint16_t *)(m->arena + off), (const uint16_t *)src, rows, K, mode, (mode == 0 || mode == 3) ? row0 / 32 : 0, st);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return sev_fail(SEV_EHIP, "load_tensor: %s", hipGetErrorString(e));
@@ -233,7 +234,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->max_items = bf ? ATT_ITEMS_CAP : 1;
     kv->max_groups = bf ? (int)(rows_pad * G / 32 + SEV_MAX_BATCH) : 1;
     const size_t n_qkv = m->n_qkv;
-    kv->part_elems = rows_pad * std::max<size_t>(16 * std::max<size_t>(n_qkv, d.d_model), 2 * (size_t)d.d_ffn);
+    kv->part_elems = rows_pad * std::max<size_t>(16 * std::max<size_t>(n_qkv, d.d_model), 4 * (size_t)d.d_ffn);
 
     // carve the workspace
     size_t off = 0;
@@ -249,7 +250,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     const size_t o_pp = take((size_t)max_requests * SEV_MAX_DRAFT * 4);
     const size_t o_err = take(4);
     const size_t o_rq = take(4 * (size_t)(SEV_MAX_BATCH + 1) * 4);
-    const size_t o_row = take(4 * rows_pad * 4);
+    const size_t o_row = take(5 * rows_pad * 4);
     const size_t o_anc = take(rows_pad * 8);
     const size_t o_cs = take(rows_pad * (d.head_dim / 2) * 8);
     const size_t o_it = take((size_t)kv->max_items * (32 + SEV_ATT_MAX_CP * 4));
@@ -266,6 +267,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     const size_t o_li = take(bf ? (size_t)(d.vocab / 32 + 4) * rows_pad * 4 : 4);
     const size_t o_am = take(rows_pad * 4);
     const size_t o_lg = take(bf ? 4 : rows_pad * (size_t)d.vocab * 4);
+    const size_t o_ssq = take(2 * rows_pad * 8);
     kv->ws_bytes = off;
     hipError_t e = hipMalloc((void **)&kv->ws, kv->ws_bytes);
     if (e != hipSuccess) {
@@ -298,6 +300,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->plan.row_node = rw + rows_pad;
     kv->plan.row_pos = rw + 2 * rows_pad;
     kv->plan.row_tok = rw + 3 * rows_pad;
+    kv->plan.row_kvloc = rw + 4 * rows_pad;
     kv->plan.row_anc = (unsigned long long *)(w + o_anc);
     kv->plan.row_cs = (float2 *)(w + o_cs);
     kv->plan.it_a = (int4 *)(w + o_it);
@@ -320,6 +323,8 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->lm_idx = (int32_t *)(w + o_li);
     kv->row_argmax = (int32_t *)(w + o_am);
     kv->logits_f32 = (float *)(w + o_lg);
+    kv->ssq[0] = (unsigned long long *)(w + o_ssq);
+    kv->ssq[1] = kv->ssq[0] + rows_pad;
     launch_fill_i32(kv->next_tok, -1, max_requests, 0);
     e = hipDeviceSynchronize();
     if (e != hipSuccess) {

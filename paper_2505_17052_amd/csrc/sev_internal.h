@@ -63,6 +63,7 @@ struct DevPlan {
     int32_t *req_slot, *req_P, *req_n, *req_row0;
     // per row (draft node)
     int32_t *row_req, *row_node, *row_pos, *row_tok;
+    int32_t *row_kvloc;       // physical page * 16 + token in page of the cache position P + node the row is written to
     unsigned long long *row_anc;
     float2 *row_cs;           // [rows][hd/2] (cos, sin) of pos * theta_i
     // attention work items (bf16 path): a = {row group, first page, pages, prefix length},
@@ -102,8 +103,9 @@ struct sev_kv {
 
     // activations
     float *h;                 // [rows][d] residual stream
-    float *part;              // split-K partial sums / f32 scratch
+    float *part;              // split-K exchange buffer / f32 scratch
     size_t part_elems;
+    unsigned long long *ssq[2];   // bf16: fixed-point sums of squares of the residual rows (two buffers, used alternately)
     void *xa;                 // normed activations (xpack for bf16, [rows][d] f32 otherwise)
     void *q_buf;              // bf16: q hi/lo planes [2][rows][Hq*hd]; f32: qkv [rows][n_qkv]
     void *o_buf;              // attention output (xpack K=q_dim, or f32 [rows][q_dim])
