@@ -734,21 +734,24 @@ __global__ __launch_bounds__(256) void lm_reduce_kernel(const float *val, const 
 //
 // Work item = (request, group of 32 query rows, KV chunk) x KV head.  The 32 rows are
 // (query head in the GQA group) x (draft node), so every K/V byte is read once for the whole
-// group.  The 4 waves of a block take alternate page pairs of the chunk; each wave runs
-//   S^T = K Q^T   : MFMA 16x16x32, A = one page of keys (16 keys x 32 dims: one coalesced 1 KiB
-//                   load thanks to the in-page layout), B = q (hi and lo planes)
-//   O^T += V^T P^T: MFMA 16x16x32 over a pair of pages; the S^T register layout IS the B-operand
-//                   layout of P^T, so probabilities never leave registers
-// with an online softmax per query row; then the waves' partial (max, sum, O) are merged through
-// LDS and written out for the cross-chunk merge.  Masking: keys < P are visible to every row;
-// key P + j is visible to a row iff bit j of the row's ancestor mask is set.
+// group.  The 4 waves of a block take alternate page pairs (32 keys) of the chunk; per pair a wave runs
+//   S^T = K Q^T   : 8 k-steps of MFMA 32x32x16, A = keys (32 keys x 16 dims; the in-page K layout
+//                   makes every 16-lane group read 256 contiguous bytes), B = q (hi and lo planes,
+//                   kept in registers for the whole chunk)
+//   O^T += V^T P^T: MFMA 32x32x16 per 32-dim tile and page; a lane of the S^T result holds 16 keys of
+//                   ONE query, and the in-page V layout is chosen so that exactly those keys are the
+//                   contraction slots of the lane's B operand: probabilities never leave registers
+// with an online softmax per query row (one cross-lane exchange per pair: the other 16 keys of the
+// row sit in lane ^ 32); then the waves' partial (max, sum, O) are merged through LDS and written
+// out for the cross-chunk merge.  Masking: keys < P are visible to every row; key P + j is visible
+// to a row iff bit j of the row's ancestor mask is set.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g, int layer, int Hq,
                                                            float *att_o, float2 *att_ml, float scale_log2e) {
-    extern __shared__ float lds[];                    // two merge slots (64 accumulator registers + max + sum per lane), then the q fragments
+    extern __shared__ float lds[];                    // two merge slots: 64 accumulator registers + max + sum per lane
     SEV_TRACE_T(tr0);
     const int item = blockIdx.x, kvh = blockIdx.y;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar: loop bounds stay uniform
     // everything the block needs to know comes from two 16-byte loads and one page-id load, all independent
     const int4 ia = p.it_a[item], ib = p.it_b[item];
     const int rg = ia.x, page0 = ia.y, npages = ia.z, P = ia.w, n = ib.x, row0 = ib.y;
@@ -757,150 +760,127 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
     int pt_val;                                         // lane j < 32: page (j&1) of this wave's pair j/2
     {
         const int pidx = 2 * (wave + 4 * ((lane & 31) >> 1)) + (lane & 1);
-        pt_val = p.it_pages[(size_t)item * SEV_ATT_MAX_CP + min(pidx, npages - 1)];
+        pt_val = p.it_pages[(size_t)item * SEV_ATT_MAX_CP + pidx];    // the list is padded with the last page
     }
     const int G = Hq / g.Hkv;
-    const int qi = lane & 15, grp = lane >> 4;
-    const char *Kl = g.pool + (size_t)layer * g.layer_stride + (size_t)kvh * 4096 + lane * 16;
-    const char *Vl = Kl + g.v_offset;
+    const int qrow = lane & 31, half = lane >> 5;
     const size_t page_stride = (size_t)g.Hkv * 4096;
     const size_t qd = (size_t)Hq * 128;
+    // K fragment of k-step ks: lane (key = lane % 32 -> page (key / 16), token key % 16; dims 16 ks + 8 half .. +7)
+    //   byte offset in the page block: ((2 ks + half) * 16 + token) * 16
+    // V fragment of (dim tile dt, page): lane (dim = lane % 32, half) -> 16 bytes at ((dt * 64 + lane) * 16)
+    const char *Kl = g.pool + (size_t)layer * g.layer_stride + (size_t)kvh * 4096 + (half * 16 + (lane & 15)) * 16;
+    const char *Vl = g.pool + (size_t)layer * g.layer_stride + g.v_offset + (size_t)kvh * 4096 + lane * 16;
+    const int kpage_sel = (lane >> 4) & 1;             // which page of the pair this lane's key belongs to
 
-    // Query fragments go to LDS once per block, in B-operand order [plane][q tile][k step][lane]
-    // (lane (q = lane%16, c = lane/16) holds dims 32*step + 8c .. +7 of row q); every wave re-reads them
-    // per page pair, which keeps 64 registers free for a second resident block per compute unit.
-    u32x4 *qs = (u32x4 *)(lds + 2 * 64 * 64 + 2 * 2 * 2 * 64);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int e = threadIdx.x + 256 * i;            // 0..1023 = [pl 2][qt 2][st 4][lane 64]
-        const int ln = e & 63, st = (e >> 6) & 3, qt = (e >> 8) & 1, pl = e >> 9;
-        const int R = rg * 32 + qt * 16 + (ln & 15);
-        u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-        if (R < G * n) {
-            const int hg = R / n, node = R - hg * n;
-            v = *(const u32x4 *)(q_planes + (size_t)pl * M * qd + (size_t)(row0 + node) * qd + (size_t)(kvh * G + hg) * 128 +
-                                 8 * (ln >> 4) + 32 * st);
-        }
-        qs[e] = v;
-    }
-    unsigned long long anc[2];
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        const int R = rg * 32 + qt * 16 + qi;
-        anc[qt] = 0ull;
-        if (R < G * n) anc[qt] = p.row_anc[row0 + R % n];
-    }
-
-    f32x4 oacc[8][2];
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) oacc[t][qt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
-
-    // K and V of a page pair live in one register set each; the next pair's keys are requested as soon
-    // as the score MFMAs have consumed the current ones, the next values right after the PV MFMAs, so
-    // both latencies hide behind the other half of the pair's work.
-    u32x4 k0[4], k1[4], v0[4], v1[4];
+    // K and V fragments of one page pair live in registers; the keys of the next pair are requested as
+    // soon as the score MFMAs have consumed the current ones, the values right after the PV MFMAs.  Two
+    // blocks share a compute unit, so the other block's waves fill the time a wave waits for its loads.
+    u32x4 kf[8], vf[2][4];
     auto load_k = [&](int i) {
-        const char *a0 = Kl + (size_t)__shfl(pt_val, 2 * i) * page_stride, *a1 = Kl + (size_t)__shfl(pt_val, 2 * i + 1) * page_stride;
+        const int pg = __shfl(pt_val, 2 * i + kpage_sel);
+        const char *a = Kl + (size_t)pg * page_stride;
 #pragma unroll
-        for (int st = 0; st < 4; ++st) {
-            k0[st] = *(const u32x4 *)(a0 + st * 1024);
-            k1[st] = *(const u32x4 *)(a1 + st * 1024);
-        }
+        for (int ks = 0; ks < 8; ++ks) kf[ks] = *(const u32x4 *)(a + ks * 512);
     };
     auto load_v = [&](int i) {
         const char *a0 = Vl + (size_t)__shfl(pt_val, 2 * i) * page_stride, *a1 = Vl + (size_t)__shfl(pt_val, 2 * i + 1) * page_stride;
 #pragma unroll
-        for (int tp = 0; tp < 4; ++tp) {
-            v0[tp] = *(const u32x4 *)(a0 + tp * 1024);
-            v1[tp] = *(const u32x4 *)(a1 + tp * 1024);
+        for (int dt = 0; dt < 4; ++dt) {
+            vf[0][dt] = *(const u32x4 *)(a0 + dt * 1024);
+            vf[1][dt] = *(const u32x4 *)(a1 + dt * 1024);
         }
     };
-    if (my_pairs > 0) {
-        load_k(0);
-        load_v(0);
+    load_k(0);                                             // padded page list: always a valid page, even for an idle wave
+    load_v(0);
+
+    // query fragments of this lane's row (hi and lo planes, 8 k-steps): 64 registers for the whole chunk
+    const int R = rg * 32 + qrow;
+    const bool row_live = R < G * n;
+    u32x4 qf[2][8];
+    unsigned long long anc = 0ull;
+    {
+        const int hg = row_live ? R / n : 0, node = row_live ? R - hg * n : 0;
+        const uint16_t *qp = q_planes + (size_t)(row0 + node) * qd + (size_t)(kvh * G + hg) * 128 + 8 * half;
+#pragma unroll
+        for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                qf[pl][ks] = *(const u32x4 *)(qp + (size_t)pl * M * qd + 16 * ks);     // dead rows read row (row0, head 0): harmless, never stored
+        anc = p.row_anc[row0 + node];
+        if (!row_live) anc = 0ull;
     }
-    __syncthreads();                                       // q fragments are in LDS
+
+    f32x16 oacc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[t][r] = 0.f;
+    float mrun = -INFINITY, lrun = 0.f;
     SEV_TRACE_T(tr1);
 
     auto pair_step = [&](int i, auto prefetch_tag) {
         constexpr bool PREFETCH = decltype(prefetch_tag)::value;
         const int lp0 = 2 * (wave + 4 * i);                 // chunk-local pages of the pair
         const bool has1 = (lp0 + 1) < npages;
-        // scores: s[page][qt] holds keys 4*grp + r of the page for query qi
-        f32x4 s[2][2];
+        // scores of this lane's query against keys 8j + 4*half + r of the pair (j = 0..3 -> register 4j + r)
+        f32x16 sh;
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < 16; ++r) sh[r] = 0.f;
 #pragma unroll
-            for (int st = 0; st < 4; ++st) {
-                const bf16x8 qh = as_bf16x8(qs[((0 * 2 + qt) * 4 + st) * 64 + lane]);
-                const bf16x8 ql = as_bf16x8(qs[((1 * 2 + qt) * 4 + st) * 64 + lane]);
-                a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0[st]), qh, a0, 0, 0, 0);
-                a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1[st]), qh, a1, 0, 0, 0);
-                a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k0[st]), ql, a0, 0, 0, 0);
-                a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(k1[st]), ql, a1, 0, 0, 0);
-            }
-            s[0][qt] = a0;
-            s[1][qt] = a1;
+        for (int ks = 0; ks < 8; ++ks) {
+            sh = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(qf[0][ks]), sh, 0, 0, 0);
+            sh = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(qf[1][ks]), sh, 0, 0, 0);
         }
         if (PREFETCH) load_k(i + 1);
-        const int j0 = (page0 + lp0) * 16 + 4 * grp - P;    // draft-node index of this lane's first key (negative: prefix)
+        const int jbase = (page0 + lp0) * 16 + 4 * half - P;    // draft-node index of key register 0 (negative: prefix)
+        // (the body of a pair step is kept free of branches: with control flow inside the loop the
+        // compiler waits for ALL outstanding loads at every merge point, which would undo the prefetch)
+        float sc[16];
+        float mx = -INFINITY;
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            uint32_t h[4], l[4];
-            float mx = -INFINITY;
+        for (int j4 = 0; j4 < 4; ++j4) {
+            // 4-bit visibility of keys j..j+3: prefix keys (index < 0) always, draft key i iff ancestor bit i
+            // (the mask has no bits at or above n); plain shifts and selects
+            const int j = jbase + 8 * j4;
+            const unsigned up = j < 64 ? (unsigned)(anc >> max(j, 0)) : 0u;             // j >= 0 (the tail of the last page can reach past 63)
+            const unsigned dn = (unsigned)((anc << (-max(j, -3))) | ((1ull << (-max(j, -3))) - 1ull));   // -3 <= j < 0
+            unsigned vis4 = j >= 0 ? up : (j <= -4 ? 0xFu : dn);
+            if (j4 >= 2) vis4 = has1 ? vis4 : 0u;
 #pragma unroll
-            for (int pg = 0; pg < 2; ++pg) {
-                // 4-bit visibility of keys j..j+3: prefix keys (index < 0) always, draft key i iff ancestor bit i
-                // (the mask has no bits at or above n); plain shifts, no branches
-                const int j = j0 + pg * 16;
-                const unsigned long long m = anc[qt];
-                const unsigned up = j < 64 ? (unsigned)(m >> max(j, 0)) : 0u;               // j >= 0 (the tail of the last page can reach past 63)
-                const unsigned dn = (unsigned)((m << (-max(j, -3))) | ((1ull << (-max(j, -3))) - 1ull));   // -3 <= j < 0
-                unsigned vis4 = j >= 0 ? up : (j <= -4 ? 0xFu : dn);
-                if (pg == 1 && !has1) vis4 = 0u;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float v = ((vis4 >> r) & 1u) ? s[pg][qt][r] * scale_log2e : -INFINITY;
-                    s[pg][qt][r] = v;
-                    mx = fmaxf(mx, v);
-                }
+            for (int r = 0; r < 4; ++r) {
+                const float v = ((vis4 >> r) & 1u) ? sh[4 * j4 + r] * scale_log2e : -INFINITY;
+                sc[4 * j4 + r] = v;
+                mx = fmaxf(mx, v);
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float mnew = fmaxf(mrun[qt], mx);
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = __builtin_amdgcn_exp2f(mrun[qt] - muse);
-            mrun[qt] = mnew;
-            float ps = 0.f;
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mnew = fmaxf(mrun, mx);
+        const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+        const float alpha = __builtin_amdgcn_exp2f(mrun - muse);
+        mrun = mnew;
+        float ps = 0.f;
+        uint32_t ph[8], pl_[8];
 #pragma unroll
-            for (int pg = 0; pg < 2; ++pg)
+        for (int r = 0; r < 16; r += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(sc[r] - muse), p1 = __builtin_amdgcn_exp2f(sc[r + 1] - muse);
+            ps += p0 + p1;
+            split_pack2(p0, p1, ph[r / 2], pl_[r / 2]);
+        }
+        lrun = lrun * alpha + ps;
 #pragma unroll
-                for (int r = 0; r < 4; r += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s[pg][qt][r] - muse), p1 = __builtin_amdgcn_exp2f(s[pg][qt][r + 1] - muse);
-                    ps += p0 + p1;
-                    split_pack2(p0, p1, h[pg * 2 + r / 2], l[pg * 2 + r / 2]);
-                }
-            lrun[qt] = lrun[qt] * alpha + ps;
-            const bf16x8 pH = as_bf16x8((u32x4){h[0], h[1], h[2], h[3]});
-            const bf16x8 pL = as_bf16x8((u32x4){l[0], l[1], l[2], l[3]});
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int tp = 0; tp < 4; ++tp) {
-                // dims tile 2tp: tokens from the low halves of the two pages' loads; tile 2tp+1: high halves
-                const bf16x8 va = as_bf16x8((u32x4){v0[tp][0], v0[tp][1], v1[tp][0], v1[tp][1]});
-                const bf16x8 vb = as_bf16x8((u32x4){v0[tp][2], v0[tp][3], v1[tp][2], v1[tp][3]});
-                f32x4 oa = oacc[2 * tp][qt], ob = oacc[2 * tp + 1][qt];
+            for (int r = 0; r < 16; ++r) oacc[t][r] *= alpha;
+        // page kk of the pair is contraction step kk: its 8 slots of this lane are score registers 8kk .. 8kk+7
 #pragma unroll
-                for (int r = 0; r < 4; ++r) { oa[r] *= alpha; ob[r] *= alpha; }
-                oa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pH, oa, 0, 0, 0);
-                oa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pL, oa, 0, 0, 0);
-                ob = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pH, ob, 0, 0, 0);
-                ob = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vb, pL, ob, 0, 0, 0);
-                oacc[2 * tp][qt] = oa;
-                oacc[2 * tp + 1][qt] = ob;
+        for (int kk = 0; kk < 2; ++kk) {
+            const bf16x8 pH = as_bf16x8((u32x4){ph[4 * kk], ph[4 * kk + 1], ph[4 * kk + 2], ph[4 * kk + 3]});
+            const bf16x8 pL = as_bf16x8((u32x4){pl_[4 * kk], pl_[4 * kk + 1], pl_[4 * kk + 2], pl_[4 * kk + 3]});
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf[kk][dt]), pH, oacc[dt], 0, 0, 0);
+                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf[kk][dt]), pL, oacc[dt], 0, 0, 0);
             }
         }
         if (PREFETCH) load_v(i + 1);
@@ -911,35 +891,33 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
 
     // ---- merge the 4 waves pairwise through LDS, in the accumulators' own register layout
     // (wave 1 -> 0 and 3 -> 2, then 2 -> 0); wave 0 writes the block's partial result.
-    float *slotO = lds;                                 // [2 slots][64 regs][64 lanes]
-    float *slotM = lds + 2 * 64 * 64;                   // [2 slots][2 qt][64 lanes] (max), then the same for sums
-    float *slotL = slotM + 2 * 2 * 64;
-    auto put = [&](int sl) {
+    f32x4 *slotO = (f32x4 *)lds;                        // [2 slots][16 register quads][64 lanes]
+    float *slotM = lds + 2 * 64 * 64;                   // [2 slots][64 lanes] (max), then the same for sums
+    float *slotL = slotM + 2 * 64;
+    auto put = [&](int sl_) {
+        slotM[sl_ * 64 + lane] = mrun;
+        slotL[sl_ * 64 + lane] = lrun;
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            slotM[(sl * 2 + qt) * 64 + lane] = mrun[qt];
-            slotL[(sl * 2 + qt) * 64 + lane] = lrun[qt];
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) slotO[(sl * 64 + (t * 2 + qt) * 4 + r) * 64 + lane] = oacc[t][qt][r];
-        }
+            for (int j = 0; j < 4; ++j)
+                slotO[(sl_ * 16 + t * 4 + j) * 64 + lane] = (f32x4){oacc[t][4 * j], oacc[t][4 * j + 1], oacc[t][4 * j + 2], oacc[t][4 * j + 3]};
     };
-    auto take = [&](int sl) {
+    auto take = [&](int sl_) {
+        const float mo = slotM[sl_ * 64 + lane], lo_ = slotL[sl_ * 64 + lane];
+        const float mnew = fmaxf(mrun, mo);
+        const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+        const float sa = exp2f(mrun - muse), sb = exp2f(mo - muse);
+        mrun = mnew;
+        lrun = lrun * sa + lo_ * sb;
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            const float mo = slotM[(sl * 2 + qt) * 64 + lane], lo_ = slotL[(sl * 2 + qt) * 64 + lane];
-            const float mnew = fmaxf(mrun[qt], mo);
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float sa = exp2f(mrun[qt] - muse), sb = exp2f(mo - muse);
-            mrun[qt] = mnew;
-            lrun[qt] = lrun[qt] * sa + lo_ * sb;
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
+            for (int j = 0; j < 4; ++j) {
+                const f32x4 o = slotO[(sl_ * 16 + t * 4 + j) * 64 + lane];
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    oacc[t][qt][r] = oacc[t][qt][r] * sa + slotO[(sl * 64 + (t * 2 + qt) * 4 + r) * 64 + lane] * sb;
-        }
+                for (int r = 0; r < 4; ++r) oacc[t][4 * j + r] = oacc[t][4 * j + r] * sa + o[r] * sb;
+            }
     };
     if (wave & 1) put(wave >> 1);
     __syncthreads();
@@ -950,18 +928,15 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
     if (wave == 0) {
         take(0);
         const size_t base = ((size_t)item * g.Hkv + kvh) * 32;
+        const float l = lrun + __shfl_xor(lrun, 32);
+        if (half == 0) att_ml[base + qrow] = make_float2(mrun, l);
+        // register 4j + r of tile t is dim 32t + 8j + 4*half + r of this lane's query
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            float l = lrun[qt];
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
-            const int q = qt * 16 + qi;
-            if (grp == 0) att_ml[base + q] = make_float2(mrun[qt], l);
+        for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int t = 0; t < 8; ++t)
-                *(float4 *)(att_o + (base + q) * 128 + t * 16 + 4 * grp) =
-                    make_float4(oacc[t][qt][0], oacc[t][qt][1], oacc[t][qt][2], oacc[t][qt][3]);
-        }
+            for (int j = 0; j < 4; ++j)
+                *(float4 *)(att_o + (base + qrow) * 128 + t * 32 + 8 * j + 4 * half) =
+                    make_float4(oacc[t][4 * j], oacc[t][4 * j + 1], oacc[t][4 * j + 2], oacc[t][4 * j + 3]);
     }
 #ifdef SEV_TRACE
     if (threadIdx.x == 0 && g_trace) {
@@ -1127,7 +1102,7 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         }
         {
             Prof p(kv, st, PROF_ATTN);
-            const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 2 * 64) * 4 + 1024 * 16;   // merge slots + q fragments
+            const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 64) * 4;   // two merge slots
             hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan, g, l,
                                d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e);
             hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,

@@ -1,4 +1,6 @@
 // Kernels shared by both precisions: call plan, acceptance, KV commit, cache import/export.
+#include <algorithm>
+
 #include "sev_internal.h"
 #include "kv_layout.h"
 
@@ -103,8 +105,9 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
             anc_prev = anc;
             depth_prev = depth;
         }
-        // attention work items of this request
+        // attention work items of this request: its pages are split evenly over my_chunks chunks
         const int pages = (P + n + SEV_PAGE - 1) / SEV_PAGE;
+        const int cpp = (pages + my_chunks - 1) / my_chunks;
         int it = s_item0[t], g0 = s_grp0[t];
         for (int rg = 0; rg < my_groups; ++rg) {
             d.p.mg_req[g0 + rg] = t;
@@ -112,18 +115,26 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
             d.p.mg_item0[g0 + rg] = it;
             d.p.mg_count[g0 + rg] = my_chunks;
             for (int c = 0; c < my_chunks; ++c, ++it) {
-                const int p0 = c * d.chunk_pages;
-                const int np = min(d.chunk_pages, pages - p0);
-                d.p.it_a[it] = make_int4(rg, p0, np, P);
-                d.p.it_b[it] = make_int4(n, row0, t, 0);
-                const int32_t *pt = d.page_table + (size_t)slot * d.max_pages;
-                for (int i = 0; i < np; ++i) d.p.it_pages[(size_t)it * SEV_ATT_MAX_CP + i] = pt[p0 + i];
+                const int p0 = c * cpp;
+                d.p.it_a[it] = make_int4(rg, p0, min(cpp, pages - p0), P);
+                d.p.it_b[it] = make_int4(n, row0, t, slot);
             }
         }
     }
-    __syncthreads();   // row_pos of every row is written (same block)
-    const int rows = s_row0[B], half = d.hd / 2;
-    for (int idx = t; idx < rows * half; idx += blockDim.x) {
+}
+
+// Second half of the plan, one thread per entry: physical page ids of every attention work item
+// (padded with the chunk's last page, so that the attention kernel can load its page ids without
+// knowing the chunk length) and the rotary table (cos, sin)(pos * theta_i), computed in double.
+__global__ __launch_bounds__(256) void plan_fill_kernel(PlanDev d, int n_items, int rows) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx < n_items * SEV_ATT_MAX_CP) {
+        const int it = idx / SEV_ATT_MAX_CP, i = idx - it * SEV_ATT_MAX_CP;
+        const int4 ia = d.p.it_a[it], ib = d.p.it_b[it];
+        d.p.it_pages[idx] = d.page_table[(size_t)ib.w * d.max_pages + ia.y + min(i, ia.z - 1)];
+    }
+    const int half = d.hd / 2;
+    if (idx < rows * half) {
         const int r = idx / half, i = idx - r * half;
         const double theta = pow(d.rope_base, -2.0 * (double)i / (double)d.hd);
         double s, c;
@@ -133,8 +144,7 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
 }
 
 void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_tokens, const int32_t *parents, int rows,
-                 int chunk_pages, hipStream_t st) {
-    (void)rows;
+                 int chunk_pages, int n_items, hipStream_t st) {
     PlanDev d;
     d.p = kv->plan;
     d.seq_len = kv->seq_len;
@@ -151,6 +161,8 @@ void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_toke
     d.page_table = kv->page_table;
     d.max_pages = kv->max_pages_per_req;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, pa, d);
+    const int64_t entries = std::max<int64_t>((int64_t)n_items * SEV_ATT_MAX_CP, (int64_t)rows * (d.hd / 2));
+    hipLaunchKernelGGL(plan_fill_kernel, dim3((unsigned)((entries + 255) / 256)), dim3(256), 0, st, d, n_items, rows);
 }
 
 // ---------------------------------------------------------------------------

@@ -9,9 +9,9 @@
 // consumes it, so that one wave reads a block with four fully coalesced 1 KiB loads:
 //   K block: [head_dim/8 chunks][16 tokens][8 elements]      — a 16x16x32 MFMA A-operand of
 //            (16 keys x 32 dims) is 64 lanes x 16 B, contiguous.
-//   V block: [4 tile pairs][64 lanes = 4 token groups x 16 dims][2 tiles][4 tokens] — lane
-//            (dim d of a 16-dim tile, token group g) finds tokens 4g..4g+3 of two adjacent
-//            dim tiles in one 16 B load.
+//   V block: [4 dim tiles of 32][64 lanes = (half h, dim d)][8 tokens] — the A-operand of a
+//            32x32x16 MFMA (32 dims x 16 tokens); lane (d, h) holds tokens 4h..4h+3 and 8+4h..8+4h+3,
+//            which are exactly the keys whose scores that lane holds after the score MFMA.
 #pragma once
 #include <stdint.h>
 
@@ -30,8 +30,8 @@ __host__ __device__ inline int k_in_page(int t, int e, int hd) {
 template <bool BF16>
 __host__ __device__ inline int v_in_page(int t, int e, int hd) {
     if (BF16) {
-        const int tile = e >> 4, di = e & 15, pair = tile >> 1, tip = tile & 1, g = t >> 2, tt = t & 3;
-        return ((((pair * 64) + g * 16 + di) * 2 + tip) << 2) + tt;
+        const int dt = e >> 5, d = e & 31, h = (t >> 2) & 1, slot = 4 * (t >> 3) + (t & 3);
+        return (((dt * 64) + h * 32 + d) << 3) + slot;
     }
     return t * hd + e;
 }

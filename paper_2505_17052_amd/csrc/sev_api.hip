@@ -481,32 +481,42 @@ extern "C" const char *sev_profile_name(int which) {
 // ---------------------------------------------------------------------------
 // verify
 // ---------------------------------------------------------------------------
+// Pages per attention chunk.  Every (request, row group, chunk, KV head) is one block with a fixed cost
+// of several microseconds (work item and page list, query fragments, wave merge, partial result) on
+// top of its page pairs, and all blocks start together: the shortest kernel is the one whose blocks
+// all run at once, one per compute unit, with chunks as small as that allows (measured on the
+// 8B-shape workloads).  Work lists that do not fit even with the largest chunks fall back to 64-page
+// chunks.  The pages of a request are then split evenly over its chunks.
 static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, int *n_groups) {
     const sev_model_desc &d = kv->model->d;
     const int G = d.n_q_heads / d.n_kv_heads;
-    // aim for a few work items per compute unit, chunks of at least 8 pages, and stay inside the item capacity
-    int64_t total_pages = 0;
-    for (int b = 0; b < pa.B; ++b) total_pages += (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE;
+    static int n_cu = 0;
+    if (!n_cu) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            v = 256;
+        n_cu = v;
+    }
     int64_t total_groups = 0;
     for (int b = 0; b < pa.B; ++b) total_groups += (G * pa.nd[b] + 31) / 32;
-    // a block of 4 waves takes alternate page pairs of its chunk; its fixed cost (query fragments,
-    // wave merge, partial result) is amortised over the chunk: aim for 8 pairs per wave (64 pages),
-    // but keep roughly one block per compute unit; never below 8 pages
-    int64_t cp = 64;
-    for (; cp > 8; cp /= 2) {
-        const int64_t blocks = (total_pages / cp + pa.B) * std::max<int64_t>(1, total_groups / pa.B) * d.n_kv_heads;
-        if (blocks >= 240) break;
-    }
-    if (const char *e = getenv("SEV_TUNE_CP")) {        // tuning experiments: pages per attention chunk
-        const int v = atoi(e);
-        if (v >= 2 && v <= SEV_ATT_MAX_CP) cp = v;
-    }
-    for (;; cp *= 2) {
+    auto items_for = [&](int64_t cp) {
         int64_t items = 0;
         for (int b = 0; b < pa.B; ++b) {
             const int64_t pages = (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE;
             items += ((G * pa.nd[b] + 31) / 32) * ((pages + cp - 1) / cp);
         }
+        return items;
+    };
+    int64_t cp = 0;
+    for (int64_t c = 8; c <= SEV_ATT_MAX_CP; c += 8)
+        if (items_for(c) * d.n_kv_heads <= (int64_t)n_cu) { cp = c; break; }
+    if (!cp) cp = 64;
+    if (const char *e = getenv("SEV_TUNE_CP")) {        // tuning experiments: pages per attention chunk
+        const int v = atoi(e);
+        if (v >= 2 && v <= SEV_ATT_MAX_CP) cp = v;
+    }
+    for (;; cp = std::min<int64_t>(cp * 2, SEV_ATT_MAX_CP)) {
+        const int64_t items = items_for(cp);
         if (items <= kv->max_items) {
             *n_items = (int)items;
             *n_groups = (int)total_groups;
@@ -556,7 +566,7 @@ extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_ar
     }
     {
         Prof p(kv, st, PROF_OTHER);
-        launch_plan(kv, pa, a->draft_tokens, a->parents, (int)rows, cp, st);
+        launch_plan(kv, pa, a->draft_tokens, a->parents, (int)rows, cp, n_items, st);
     }
     if (m->d.dtype == SEV_F32) f32_forward(m, kv, (int)rows, a->B, a->logits, st);
     else bf16_forward(m, kv, (int)rows, a->B, n_items, n_groups, a->logits, st);

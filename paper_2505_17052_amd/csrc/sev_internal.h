@@ -143,7 +143,7 @@ struct Prof {
 void launch_fill_f32(float *p, float v, int64_t n, hipStream_t st);
 void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t st);
 void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_tokens, const int32_t *parents, int rows,
-                 int chunk_pages, hipStream_t st);
+                 int chunk_pages, int n_items, hipStream_t st);
 void launch_accept(const sev_kv *kv, int B, int k_max, int mode, const int32_t *draft_tokens, const int32_t *parents,
                    int32_t *accept_len, int32_t *bonus, int32_t *accept_path, hipStream_t st);
 void launch_commit(const sev_kv *kv, const int32_t *slots_dev_by_value, int B, bool rollback, hipStream_t st);
