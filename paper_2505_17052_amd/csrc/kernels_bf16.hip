@@ -172,8 +172,8 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, cons
 // skinny-M GEMM on the matrix cores:  Y[M][N] = X[M][K] * W[N][K]^T, with the stage that follows
 // the GEMM fused into its epilogue.
 //
-// A block of 4 waves covers up to 128 rows (MT tiles of 32) and 4*NT column tiles of 32; wave w
-// owns NT column tiles.  Weights go global -> registers, one fully coalesced 1 KiB fragment per
+// A block of 4 waves covers up to 128 rows (MT tiles of 32) and 4*NT column tiles of 32 (NT = 1, 2, or 4
+// with all 256 accumulator registers in use); wave w owns NT column tiles.  Weights go global -> registers, one fully coalesced 1 KiB fragment per
 // load, PF stages ahead; each weight byte is read once per row block.  Activations (hi and lo
 // planes, already in fragment order) go global -> LDS once per block and are shared by the 4 waves.
 // MFMA 32x32x16: A = weight tile (32 n x 16 k), B = activation tile (16 k x 32 m), so a lane ends up
@@ -426,10 +426,14 @@ extern "C" int sev_trace_read(unsigned long long *host, int cap) {
 
 template <int MT, int NT, int EPI, int PF>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
-    extern __shared__ u32x4 xs[];                       // [2 buffers][2 k-steps][MT][2 planes][64 lanes]
+    // a pipeline stage is KS k-steps of 16: two for the narrow tiles, one for NT = 4 (same 32 MFMAs per wave with MT = 4)
+    constexpr int KS = NT == 4 ? 1 : 2;
+    constexpr int XI = KS * MT / 2;                     // 16-byte activation loads per thread and stage
+    static_assert(KS * MT % 2 == 0, "a stage of activations must be a whole number of 4 KiB");
+    extern __shared__ u32x4 xs[];                       // [2 buffers][KS k-steps][MT][2 planes][64 lanes]
     __shared__ float red[4][128];
     SEV_TRACE_T(tr0);
-    constexpr int STAGE_U4 = 2 * MT * 2 * 64;           // uint4 per stage
+    constexpr int STAGE_U4 = KS * MT * 2 * 64;          // uint4 per stage
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // Block index decode, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, each with its
     // own L2.  Blocks that share weight tiles (the row blocks of one column group) get ids 8 apart,
@@ -442,7 +446,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     if (cg >= g.col_groups) return;                      // whole block leaves before any barrier
     const int tile0 = (cg * 4 + wave) * NT;
     const int mt0 = mb * MT;
-    const int n_stages = g.k_steps >> 1;
+    const int n_stages = g.k_steps / KS;
     const int s_begin = (int)((int64_t)n_stages * split / g.splits);
     const int s_end = (int)((int64_t)n_stages * (split + 1) / g.splits);
     const int n = s_end - s_begin;
@@ -476,25 +480,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // of PF stages: padded stages re-load the last stage (cached) and feed zero activations.
     // Weights are read exactly once per row block: their loads carry the streaming (non-temporal) hint.
     static_assert(PF % 2 == 0, "LDS buffer parity must follow the slot index");
-    u32x4 wreg[PF][NT][2];
-    u32x4 xreg[PF][MT];
-    u32x4 xf[2][MT][2];
-    const u32x4 *xsrc[MT];
+    u32x4 wreg[PF][NT][KS];
+    u32x4 xreg[PF][XI];
+    u32x4 xf[KS][MT][2];
+    const u32x4 *xsrc[XI];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
+    for (int i = 0; i < XI; ++i) {
         const int u = threadIdx.x + 256 * i;
         const int ksl = u / (MT * 128), within = u - ksl * (MT * 128);
         xsrc[i] = (const u32x4 *)g.X + ((size_t)ksl * g.m_tiles_total + mt0) * 128 + within;
     }
-    const size_t x_stage = (size_t)2 * g.m_tiles_total * 128;      // 16-byte units per stage of all row tiles
+    const size_t x_stage = (size_t)KS * g.m_tiles_total * 128;      // 16-byte units per stage of all row tiles
     const int s_last_stage = s_end - 1;
     const int n_pad = (n + PF - 1) / PF * PF;
     const u32x4 zero4 = (u32x4){0u, 0u, 0u, 0u};
 
     {
-        u32x4 x0[MT], x1[MT];
+        u32x4 x0[XI], x1[XI];
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
+        for (int i = 0; i < XI; ++i) {
             x0[i] = xsrc[i][(size_t)s_begin * x_stage];
             x1[i] = xsrc[i][(size_t)min(s_begin + 1, s_last_stage) * x_stage];
         }
@@ -502,14 +506,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         for (int u = 0; u < PF; ++u) {
             const int sx = min(s_begin + u + 2, s_last_stage), sw = min(s_begin + u, s_last_stage);
 #pragma unroll
-            for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+            for (int i = 0; i < XI; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
 #pragma unroll
             for (int a = 0; a < NT; ++a)
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(2 * sw + ks) * 64]);
+                for (int ks = 0; ks < KS; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
         }
 #pragma unroll
-        for (int i = 0; i < MT; ++i) {
+        for (int i = 0; i < XI; ++i) {
             xs[threadIdx.x + 256 * i] = x0[i];
             xs[STAGE_U4 + threadIdx.x + 256 * i] = (1 < n) ? x1[i] : zero4;
         }
@@ -517,7 +521,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     __syncthreads();
     SEV_TRACE_T(tr1);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int b = 0; b < MT; ++b)
 #pragma unroll
@@ -529,7 +533,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             const int st = base + u;
             const u32x4 *xnext = xs + ((u + 1) & 1) * STAGE_U4 + lane;      // X(st+1)
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
+            for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
                 for (int b = 0; b < MT; ++b) {
 #pragma unroll
@@ -544,7 +548,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             }
             // interleave: after every NT*2 MFMAs (one fragment pair consumed) issue its two LDS refills
 #pragma unroll
-            for (int i = 0; i < 2 * MT; ++i) {
+            for (int i = 0; i < KS * MT; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 2 * NT, 0);   // MFMA
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // DS read
             }
@@ -553,16 +557,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             const bool live = st + 2 < n;
             u32x4 *xd = xs + (u & 1) * STAGE_U4 + threadIdx.x;
 #pragma unroll
-            for (int i = 0; i < MT; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
+            for (int i = 0; i < XI; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
             __builtin_amdgcn_sched_barrier(0);
             // refill this slot: activations first, then weights (the order they will be waited on)
             const int sx = min(s_begin + st + PF + 2, s_last_stage), sw = min(s_begin + st + PF, s_last_stage);
 #pragma unroll
-            for (int i = 0; i < MT; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+            for (int i = 0; i < XI; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
 #pragma unroll
             for (int a = 0; a < NT; ++a)
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(2 * sw + ks) * 64]);
+                for (int ks = 0; ks < KS; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
         }
@@ -1002,6 +1006,7 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
     GemmCfg c;
     c.MT = (which == G_LM && m_tiles >= 3) ? 4 : (m_tiles >= 2 ? 2 : 1);
     c.NT = (n_tiles % 2 == 0) ? 2 : 1;
+    if (which == G_LM && c.MT == 4) c.NT = 4;            // never split: the widest tile halves the activation re-reads
     c.PF = 4;
     c.S = 1;
     const bool splittable = which != G_LM;
@@ -1015,10 +1020,10 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
     }
     if (const char *e = getenv(names[which])) {
         int mt, nt, sp, pf;
-        if (sscanf(e, "%d,%d,%d,%d", &mt, &nt, &sp, &pf) == 4 && (mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2) &&
+        if (sscanf(e, "%d,%d,%d,%d", &mt, &nt, &sp, &pf) == 4 && (mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2 || (nt == 4 && mt == 4 && pf == 4)) &&
             sp >= 1 && sp <= 32 && (pf == 4 || (pf == 6 && mt <= 2))) {
             c.MT = std::min(mt, m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1));
-            c.NT = nt;
+            c.NT = (nt == 4 && c.MT != 4) ? 2 : nt;
             c.PF = pf;
             if (splittable) c.S = sp;
         }
@@ -1040,14 +1045,15 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     ga.nt = c.NT;
     const int g8 = (ga.col_groups + 7) / 8 * 8;
     dim3 grid((unsigned)(g8 * ga.m_blocks * ga.splits));
-    const size_t lds = (size_t)2 * 2 * c.MT * 2 * 64 * 16;
+    const size_t lds = (size_t)2 * (c.NT == 4 ? 1 : 2) * c.MT * 2 * 64 * 16;
 #define SEV_LAUNCH(MT_, NT_, PF_)                                                                                     \
     hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, PF_>), grid, dim3(256), lds, st, ga)
 #define SEV_BY_NT(MT_, PF_)                                                                                           \
     do {                                                                                                              \
         if (c.NT == 2) SEV_LAUNCH(MT_, 2, PF_); else SEV_LAUNCH(MT_, 1, PF_);                                         \
     } while (0)
-    if (c.MT == 4) SEV_BY_NT(4, 4);
+    if (c.MT == 4 && c.NT == 4) SEV_LAUNCH(4, 4, 4);
+    else if (c.MT == 4) SEV_BY_NT(4, 4);
     else if (c.MT == 2) { if (c.PF == 6) SEV_BY_NT(2, 6); else SEV_BY_NT(2, 4); }
     else { if (c.PF == 6) SEV_BY_NT(1, 6); else SEV_BY_NT(1, 4); }
 #undef SEV_BY_NT
