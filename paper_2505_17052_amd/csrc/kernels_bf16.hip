@@ -1007,6 +1007,10 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
     c.MT = (which == G_LM && m_tiles >= 3) ? 4 : (m_tiles >= 2 ? 2 : 1);
     c.NT = (n_tiles % 2 == 0) ? 2 : 1;
     if (which == G_LM && c.MT == 4) c.NT = 4;            // never split: the widest tile halves the activation re-reads
+    if (which == G_GU && m_tiles >= 4 && ((m_tiles + 3) / 4) * ((n_tiles + 15) / 16) >= 200) {
+        c.MT = 4;                                        // enough rows to fill the chip with 128 x 512 blocks, no split needed
+        c.NT = 4;
+    }
     c.PF = 4;
     c.S = 1;
     const bool splittable = which != G_LM;
@@ -1014,9 +1018,17 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
         return ((n_tiles + 4 * x.NT - 1) / (4 * x.NT)) * ((m_tiles + x.MT - 1) / x.MT);
     };
     if (splittable) {
-        const int blocks = blocks_of(c);
-        c.S = std::min(16, std::max(1, 256 / blocks));
-        c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));          // at least 8 stages per slice
+        auto pick_s = [&]() {
+            const int blocks = blocks_of(c);
+            c.S = std::min(16, std::max(1, 256 / blocks));
+            c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));      // at least 8 stages per slice
+        };
+        pick_s();
+        // short slices are mostly pipeline fill: halve the block width instead of splitting that deep
+        if (c.NT == 2 && c.S > 1 && (k_steps / 2) / c.S < 24) {
+            c.NT = 1;
+            pick_s();
+        }
     }
     if (const char *e = getenv(names[which])) {
         int mt, nt, sp, pf;
