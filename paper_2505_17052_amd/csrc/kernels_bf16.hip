@@ -738,7 +738,8 @@ __global__ __launch_bounds__(256) void lm_reduce_kernel(const float *val, const 
 //
 // Work item = (request, group of 32 query rows, KV chunk) x KV head.  The 32 rows are
 // (query head in the GQA group) x (draft node), so every K/V byte is read once for the whole
-// group.  The 4 waves of a block take alternate page pairs (32 keys) of the chunk; per pair a wave runs
+// group.  The waves of a block (4, or 8 when a block takes a whole sequence) take alternate page pairs
+// (32 keys) of the chunk; per pair a wave runs
 //   S^T = K Q^T   : 8 k-steps of MFMA 32x32x16, A = keys (32 keys x 16 dims; the in-page K layout
 //                   makes every 16-lane group read 256 contiguous bytes), B = q (hi and lo planes,
 //                   kept in registers for the whole chunk)
@@ -746,13 +747,16 @@ __global__ __launch_bounds__(256) void lm_reduce_kernel(const float *val, const 
 //                   ONE query, and the in-page V layout is chosen so that exactly those keys are the
 //                   contraction slots of the lane's B operand: probabilities never leave registers
 // with an online softmax per query row (one cross-lane exchange per pair: the other 16 keys of the
-// row sit in lane ^ 32); then the waves' partial (max, sum, O) are merged through LDS and written
-// out for the cross-chunk merge.  Masking: keys < P are visible to every row; key P + j is visible
+// row sit in lane ^ 32); then the waves' partial (max, sum, O) are merged through LDS.  A block that
+// saw only a chunk writes its partial result for the cross-chunk merge; a block that saw the whole
+// sequence (DIRECT) normalises and writes the O projection's operand itself.  Masking: keys < P are visible to every row; key P + j is visible
 // to a row iff bit j of the row's ancestor mask is set.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g, int layer, int Hq,
-                                                           float *att_o, float2 *att_ml, float scale_log2e) {
-    extern __shared__ float lds[];                    // two merge slots: 64 accumulator registers + max + sum per lane
+template <int WAVES, bool DIRECT>
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g, int layer, int Hq,
+                                                                                    float *att_o, float2 *att_ml, float scale_log2e,
+                                                                                    uint16_t *o_pack, int m_tiles) {
+    extern __shared__ float lds[];                    // WAVES/2 merge slots: 64 accumulator registers + max + sum per lane
     SEV_TRACE_T(tr0);
     const int item = blockIdx.x, kvh = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar: loop bounds stay uniform
@@ -760,10 +764,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
     const int4 ia = p.it_a[item], ib = p.it_b[item];
     const int rg = ia.x, page0 = ia.y, npages = ia.z, P = ia.w, n = ib.x, row0 = ib.y;
     const int npairs = (npages + 1) >> 1;
-    const int my_pairs = npairs > wave ? (npairs - wave + 3) >> 2 : 0;       // this wave takes pairs wave, wave+4, ...
+    const int my_pairs = npairs > wave ? (npairs - wave + WAVES - 1) / WAVES : 0;   // this wave takes pairs wave, wave+WAVES, ...
     int pt_val;                                         // lane j < 32: page (j&1) of this wave's pair j/2
     {
-        const int pidx = 2 * (wave + 4 * ((lane & 31) >> 1)) + (lane & 1);
+        const int pidx = 2 * (wave + WAVES * ((lane & 31) >> 1)) + (lane & 1);
         pt_val = p.it_pages[(size_t)item * SEV_ATT_MAX_CP + pidx];    // the list is padded with the last page
     }
     const int G = Hq / g.Hkv;
@@ -825,7 +829,7 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
 
     auto pair_step = [&](int i, auto prefetch_tag) {
         constexpr bool PREFETCH = decltype(prefetch_tag)::value;
-        const int lp0 = 2 * (wave + 4 * i);                 // chunk-local pages of the pair
+        const int lp0 = 2 * (wave + WAVES * i);             // chunk-local pages of the pair
         const bool has1 = (lp0 + 1) < npages;
         // scores of this lane's query against keys 8j + 4*half + r of the pair (j = 0..3 -> register 4j + r)
         f32x16 sh;
@@ -893,11 +897,11 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
     if (my_pairs > 0) pair_step(my_pairs - 1, std::false_type{});
     SEV_TRACE_T(tr2);
 
-    // ---- merge the 4 waves pairwise through LDS, in the accumulators' own register layout
-    // (wave 1 -> 0 and 3 -> 2, then 2 -> 0); wave 0 writes the block's partial result.
-    f32x4 *slotO = (f32x4 *)lds;                        // [2 slots][16 register quads][64 lanes]
-    float *slotM = lds + 2 * 64 * 64;                   // [2 slots][64 lanes] (max), then the same for sums
-    float *slotL = slotM + 2 * 64;
+    // ---- merge the waves pairwise through LDS, in the accumulators' own register layout (a binary
+    // tree: wave w + stride -> wave w); wave 0 ends up with the block's result.
+    f32x4 *slotO = (f32x4 *)lds;                        // [WAVES/2 slots][16 register quads][64 lanes]
+    float *slotM = lds + (WAVES / 2) * 64 * 64;         // [slots][64 lanes] (max), then the same for sums
+    float *slotL = slotM + (WAVES / 2) * 64;
     auto put = [&](int sl_) {
         slotM[sl_ * 64 + lane] = mrun;
         slotL[sl_ * 64 + lane] = lrun;
@@ -923,24 +927,44 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_kernel(const uint16_t *q_pla
                 for (int r = 0; r < 4; ++r) oacc[t][4 * j + r] = oacc[t][4 * j + r] * sa + o[r] * sb;
             }
     };
-    if (wave & 1) put(wave >> 1);
-    __syncthreads();
-    if (!(wave & 1)) take(wave >> 1);
-    __syncthreads();
-    if (wave == 2) put(0);
-    __syncthreads();
+#pragma unroll
+    for (int stride = 1; stride < WAVES; stride *= 2) {
+        if (wave % (2 * stride) == stride) put(wave / (2 * stride));
+        __syncthreads();
+        if (wave % (2 * stride) == 0) take(wave / (2 * stride));
+        __syncthreads();
+    }
     if (wave == 0) {
-        take(0);
-        const size_t base = ((size_t)item * g.Hkv + kvh) * 32;
         const float l = lrun + __shfl_xor(lrun, 32);
-        if (half == 0) att_ml[base + qrow] = make_float2(mrun, l);
         // register 4j + r of tile t is dim 32t + 8j + 4*half + r of this lane's query
+        if constexpr (DIRECT) {
+            // the block saw the whole sequence: normalise and write hi/lo fragments for the O projection
+            if (row_live) {
+                const float inv = 1.0f / l;
+                const int hg = R / n, node = R - hg * n;
+                const int m = row0 + node, k0 = (kvh * G + hg) * 128 + 4 * half;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+                for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *(float4 *)(att_o + (base + qrow) * 128 + t * 32 + 8 * j + 4 * half) =
-                    make_float4(oacc[t][4 * j], oacc[t][4 * j + 1], oacc[t][4 * j + 2], oacc[t][4 * j + 3]);
+                    for (int j = 0; j < 4; ++j) {
+                        uint32_t hi[2], lo[2];
+                        split_pack2(oacc[t][4 * j] * inv, oacc[t][4 * j + 1] * inv, hi[0], lo[0]);
+                        split_pack2(oacc[t][4 * j + 2] * inv, oacc[t][4 * j + 3] * inv, hi[1], lo[1]);
+                        const int kk = k0 + t * 32 + 8 * j;
+                        *(uint2 *)(o_pack + xpack_index(m, kk, 0, m_tiles)) = make_uint2(hi[0], hi[1]);
+                        *(uint2 *)(o_pack + xpack_index(m, kk, 1, m_tiles)) = make_uint2(lo[0], lo[1]);
+                    }
+            }
+        } else {
+            const size_t base = ((size_t)item * g.Hkv + kvh) * 32;
+            if (half == 0) att_ml[base + qrow] = make_float2(mrun, l);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *(float4 *)(att_o + (base + qrow) * 128 + t * 32 + 8 * j + 4 * half) =
+                        make_float4(oacc[t][4 * j], oacc[t][4 * j + 1], oacc[t][4 * j + 2], oacc[t][4 * j + 3]);
+        }
     }
 #ifdef SEV_TRACE
     if (threadIdx.x == 0 && g_trace) {
@@ -1077,8 +1101,8 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     }
 }
 
-void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, float *logits_out,
-                  hipStream_t st) {
+void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, bool att_direct,
+                  float *logits_out, hipStream_t st) {
     (void)B;
     const sev_model_desc &d = m->d;
     KvGeom g = sev_kv_geom(kv);
@@ -1120,11 +1144,17 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         }
         {
             Prof p(kv, st, PROF_ATTN);
-            const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 64) * 4;   // two merge slots
-            hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan, g, l,
-                               d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e);
-            hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
-                               kv->plan, d.n_q_heads, d.n_kv_heads, op, m_tiles);
+            if (att_direct) {                            // one block of 8 waves per (request, row group, KV head): no chunks, no merge
+                const size_t lds = (size_t)(4 * 64 * 64 + 2 * 4 * 64) * 4;
+                hipLaunchKernelGGL((attn_bf16_kernel<8, true>), dim3(n_items, d.n_kv_heads), dim3(512), lds, st, qp, rows, kv->plan,
+                                   g, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
+            } else {
+                const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 64) * 4;   // two merge slots
+                hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan,
+                                   g, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
+                hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
+                                   kv->plan, d.n_q_heads, d.n_kv_heads, op, m_tiles);
+            }
         }
         {   // output projection; residual add, FFN-norm operand and scale in its epilogue
             Prof p(kv, st, PROF_GEMM_O);

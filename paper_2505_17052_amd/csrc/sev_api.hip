@@ -487,7 +487,7 @@ extern "C" const char *sev_profile_name(int which) {
 // all run at once, one per compute unit, with chunks as small as that allows (measured on the
 // 8B-shape workloads).  Work lists that do not fit even with the largest chunks fall back to 64-page
 // chunks.  The pages of a request are then split evenly over its chunks.
-static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, int *n_groups) {
+static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, int *n_groups, bool *direct) {
     const sev_model_desc &d = kv->model->d;
     const int G = d.n_q_heads / d.n_kv_heads;
     static int n_cu = 0;
@@ -507,22 +507,37 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
         }
         return items;
     };
+    // Whole sequences: when every request is short (64 pages: at most 4 page pairs per wave) and there are
+    // enough (request, row group, KV head) blocks for half the chip, a block of 8 waves takes the whole
+    // sequence and writes the attention output itself: no partial results, no merge kernel.  Longer
+    // sequences are faster split over several compute units (measured on the 8B-shape workloads: one
+    // compute unit needs about 0.75 us per page pair and SIMD).
+    *direct = false;
+    int64_t max_pages = 0;
+    for (int b = 0; b < pa.B; ++b) max_pages = std::max<int64_t>(max_pages, (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE);
+    if (!getenv("SEV_TUNE_CP") && max_pages <= 64 && total_groups * d.n_kv_heads * 2 >= n_cu &&
+        total_groups <= kv->max_items) {
+        *direct = true;
+        *n_items = (int)total_groups;
+        *n_groups = (int)total_groups;
+        return SEV_ATT_MAX_CP;
+    }
     int64_t cp = 0;
-    for (int64_t c = 8; c <= SEV_ATT_MAX_CP; c += 8)
+    for (int64_t c = 8; c <= SEV_ATT_MAX_CHUNK; c += 8)
         if (items_for(c) * d.n_kv_heads <= (int64_t)n_cu) { cp = c; break; }
     if (!cp) cp = 64;
     if (const char *e = getenv("SEV_TUNE_CP")) {        // tuning experiments: pages per attention chunk
         const int v = atoi(e);
-        if (v >= 2 && v <= SEV_ATT_MAX_CP) cp = v;
+        if (v >= 2 && v <= SEV_ATT_MAX_CHUNK) cp = v;
     }
-    for (;; cp = std::min<int64_t>(cp * 2, SEV_ATT_MAX_CP)) {
+    for (;; cp = std::min<int64_t>(cp * 2, SEV_ATT_MAX_CHUNK)) {
         const int64_t items = items_for(cp);
         if (items <= kv->max_items) {
             *n_items = (int)items;
             *n_groups = (int)total_groups;
             return (int)cp;
         }
-        if (cp >= SEV_ATT_MAX_CP) return -1;
+        if (cp >= SEV_ATT_MAX_CHUNK) return -1;
     }
 }
 
@@ -560,8 +575,9 @@ extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_ar
     if (rows > kv->max_rows) return sev_fail(SEV_ENOSPACE, "%lld draft tokens exceed max_rows=%d", (long long)rows, kv->max_rows);
     hipStream_t st = (hipStream_t)stream;
     int n_items = 0, n_groups = 0, cp = 64;
+    bool att_direct = false;
     if (m->d.dtype == SEV_BF16) {
-        cp = pick_chunk_pages(kv, pa, &n_items, &n_groups);
+        cp = pick_chunk_pages(kv, pa, &n_items, &n_groups, &att_direct);
         if (cp < 0) return sev_fail(SEV_ENOSPACE, "attention work list does not fit");
     }
     {
@@ -569,7 +585,7 @@ extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_ar
         launch_plan(kv, pa, a->draft_tokens, a->parents, (int)rows, cp, n_items, st);
     }
     if (m->d.dtype == SEV_F32) f32_forward(m, kv, (int)rows, a->B, a->logits, st);
-    else bf16_forward(m, kv, (int)rows, a->B, n_items, n_groups, a->logits, st);
+    else bf16_forward(m, kv, (int)rows, a->B, n_items, n_groups, att_direct, a->logits, st);
     {
         Prof p(kv, st, PROF_OTHER);
         launch_accept(kv, a->B, a->k_max, a->mode, a->draft_tokens, a->parents, a->accept_len, a->bonus_token,

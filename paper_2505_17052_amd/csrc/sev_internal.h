@@ -7,7 +7,8 @@
 #include "../../include/sev.h"
 
 #define SEV_PAGE 16
-#define SEV_ATT_MAX_CP 128   // pages per attention work item (chunk), upper bound
+#define SEV_ATT_MAX_CP 256   // pages per attention work item, upper bound (a block of 8 waves x 16 pairs)
+#define SEV_ATT_MAX_CHUNK 128   // pages per chunk when sequences are split over several blocks of 4 waves
 
 // ---------------------------------------------------------------------------
 // error plumbing (host)
@@ -156,5 +157,5 @@ void f32_forward(const sev_model *m, sev_kv *kv, int rows, int B, float *logits_
 
 // bf16 path
 void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int mode, int tile_add, hipStream_t st);
-void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, float *logits_out,
-                  hipStream_t st);
+void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, bool att_direct,
+                  float *logits_out, hipStream_t st);
