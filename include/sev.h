@@ -190,6 +190,26 @@ typedef struct {
 int sev_verify_ex(const sev_model *weights, sev_kv *kv_cache, const sev_verify_args *args,
                   void *stream);
 
+/* Prefill: the step before verification (appendix "Additional Details on
+ * Evaluation Setup": the prompt is prefilled on the server before decoding starts
+ * and is excluded from the reported metrics).  Appends n_tokens[b] tokens to the
+ * cache of each listed slot under a causal mask: token i of the block sits at
+ * position start_lens[b] + i and attends every position up to its own.  Nothing is
+ * accepted or rejected.  Blocks longer than the cache's row budget are processed
+ * in chunks; every chunk is committed before the next one starts.  On completion
+ * (stream order) the slot's length is start_lens[b] + n_tokens[b] and its
+ * next-token prediction is the arg-max after the last token.
+ *   slots       [host]   int32[B] or NULL (= 0..B-1)
+ *   start_lens  [host]   int32[B]; must equal the slots' current lengths (checked on the
+ *                        device: error flag bit 0 of sev_kv_get_state)
+ *   n_tokens    [host]   int32[B], each 1..t_max
+ *   tokens      [device] int32[B][t_max]; entries beyond n_tokens[b] are ignored
+ * Errors: SEV_EINVAL (null pointers, B, lengths, slots), SEV_ENOSPACE (pages of a slot do not
+ * cover start + n), SEV_EHIP.  Any pending verify of a listed slot is dropped. */
+int sev_prefill(const sev_model *weights, sev_kv *kv_cache, const int32_t *slots /*[host]*/,
+                const int32_t *start_lens /*[host]*/, const int32_t *n_tokens /*[host]*/,
+                const int32_t *tokens /*[device]*/, int B, int t_max, void *stream);
+
 /* Applies the last verify of each listed slot (paper section 4.2: the cache is
  * updated according to the accepted tokens): the accepted candidates' K/V are
  * moved to positions len..len+a-1 (chains: already in place), the slot's length

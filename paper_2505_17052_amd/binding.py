@@ -60,6 +60,7 @@ def lib():
         "sev_kv_get_state": (i32, [vp, i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint32), vp]),
         "sev_verify": (i32, [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]),
         "sev_verify_ex": (i32, [vp, vp, C.POINTER(VerifyArgs), vp]),
+        "sev_prefill": (i32, [vp, vp, vp, vp, vp, vp, i32, i32, vp]),
         "sev_kv_commit": (i32, [vp, vp, i32, vp]),
         "sev_kv_rollback": (i32, [vp, vp, i32, vp]),
         "sev_last_error": (C.c_char_p, []),
@@ -239,6 +240,14 @@ def verify_ex(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor
                    _dp(out.get("row_argmax")), _dp(out.get("logits")))
     _check(lib().sev_verify_ex(model.handle, kv.handle, C.byref(a), _stream_ptr()), "sev_verify_ex")
     return out
+
+
+def prefill(model: Model, kv: KVCache, start_lens, n_tokens, tokens: torch.Tensor, slots=None):
+    """sev_prefill: appends n_tokens[b] tokens (device int32 [B][t_max]) to each slot under a causal mask."""
+    st, nt, sl = _host_i32(start_lens), _host_i32(n_tokens), _host_i32(slots)
+    B, t_max = int(tokens.shape[0]), int(tokens.shape[1])
+    _check(lib().sev_prefill(model.handle, kv.handle, _hp(sl), _hp(st), _hp(nt), _dp(tokens), B, t_max, _stream_ptr()),
+           "sev_prefill")
 
 
 def kv_commit(kv: KVCache, slots, B: int):

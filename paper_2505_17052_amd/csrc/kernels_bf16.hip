@@ -129,11 +129,13 @@ void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int
 // QKV GEMM (which applies the row's RMS scale in its epilogue), ssq = fixed-point sum of squares.
 // ---------------------------------------------------------------------------
 // Sums of squares of the residual rows are accumulated by many blocks; they are kept as 64-bit
-// fixed point (2^-30 units) so that the atomic additions commute and the result is reproducible.
-#define SSQ_SCALE 1073741824.0f
-__device__ __forceinline__ unsigned long long ssq_fix(float v) { return (unsigned long long)(fminf(v, 8.0e9f) * SSQ_SCALE); }
+// fixed point (2^-20 units) so that the atomic additions commute and the result is reproducible.
+// One contribution (32 rows x <= 256 columns) is clamped to 1e10, so up to 1024 of them cannot wrap;
+// what is lost below 2^-20 is far under the norm's epsilon once divided by the row width.
+#define SSQ_SCALE 1048576.0f
+__device__ __forceinline__ unsigned long long ssq_fix(float v) { return (unsigned long long)(fminf(v, 1.0e10f) * SSQ_SCALE); }
 __device__ __forceinline__ float rms_scale(unsigned long long q, float inv_d, float eps) {
-    return 1.0f / sqrtf((float)((double)q * (1.0 / 1073741824.0)) * inv_d + eps);
+    return 1.0f / sqrtf((float)((double)q * (1.0 / 1048576.0)) * inv_d + eps);
 }
 
 __global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, const int32_t *row_tok, const float *g,
@@ -807,8 +809,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     const bool row_live = R < G * n;
     u32x4 qf[2][8];
     unsigned long long anc = 0ull;
+    const int hg = row_live ? R / n : 0, node = row_live ? R - hg * n : 0;
     {
-        const int hg = row_live ? R / n : 0, node = row_live ? R - hg * n : 0;
         const uint16_t *qp = q_planes + (size_t)(row0 + node) * qd + (size_t)(kvh * G + hg) * 128 + 8 * half;
 #pragma unroll
         for (int pl = 0; pl < 2; ++pl)
@@ -854,6 +856,10 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
             const unsigned up = j < 64 ? (unsigned)(anc >> max(j, 0)) : 0u;             // j >= 0 (the tail of the last page can reach past 63)
             const unsigned dn = (unsigned)((anc << (-max(j, -3))) | ((1ull << (-max(j, -3))) - 1ull));   // -3 <= j < 0
             unsigned vis4 = j >= 0 ? up : (j <= -4 ? 0xFu : dn);
+            // chains (any length): key j is visible iff j <= the row's own node index
+            const int dcs = node - j;
+            const unsigned visc = dcs >= 3 ? 0xFu : (dcs < 0 ? 0u : (2u << dcs) - 1u);
+            vis4 = p.causal ? (row_live ? visc : 0xFu) : vis4;
             if (j4 >= 2) vis4 = has1 ? vis4 : 0u;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -941,7 +947,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
             // the block saw the whole sequence: normalise and write hi/lo fragments for the O projection
             if (row_live) {
                 const float inv = 1.0f / l;
-                const int hg = R / n, node = R - hg * n;
                 const int m = row0 + node, k0 = (kvh * G + hg) * 128 + 4 * half;
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
@@ -1041,30 +1046,30 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
     auto blocks_of = [&](const GemmCfg &x) {
         return ((n_tiles + 4 * x.NT - 1) / (4 * x.NT)) * ((m_tiles + x.MT - 1) / x.MT);
     };
-    if (splittable) {
-        auto pick_s = [&]() {
-            const int blocks = blocks_of(c);
-            c.S = std::min(16, std::max(1, 256 / blocks));
-            c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));      // at least 8 stages per slice
-        };
+    auto pick_s = [&]() {
+        c.S = 1;
+        if (!splittable) return;
+        const int blocks = blocks_of(c);
+        c.S = std::min(16, std::max(1, 256 / blocks));
+        c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));          // at least 8 stages per slice
+    };
+    pick_s();
+    // short slices are mostly pipeline fill: halve the block width instead of splitting that deep
+    if (splittable && c.NT == 2 && c.S > 1 && (k_steps / 2) / c.S < 24) {
+        c.NT = 1;
         pick_s();
-        // short slices are mostly pipeline fill: halve the block width instead of splitting that deep
-        if (c.NT == 2 && c.S > 1 && (k_steps / 2) / c.S < 24) {
-            c.NT = 1;
-            pick_s();
-        }
     }
-    if (const char *e = getenv(names[which])) {
+    if (const char *e = getenv(names[which])) {          // "MT,NT,S,PF"; S = 0 keeps the automatic split
         int mt, nt, sp, pf;
         if (sscanf(e, "%d,%d,%d,%d", &mt, &nt, &sp, &pf) == 4 && (mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2 || (nt == 4 && mt == 4 && pf == 4)) &&
-            sp >= 1 && sp <= 32 && (pf == 4 || (pf == 6 && mt <= 2))) {
+            sp >= 0 && sp <= 32 && (pf == 4 || (pf == 6 && mt <= 2))) {
             c.MT = std::min(mt, m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1));
             c.NT = (nt == 4 && c.MT != 4) ? 2 : nt;
             c.PF = pf;
-            if (splittable) c.S = sp;
+            pick_s();
+            if (splittable && sp > 0) c.S = sp;
         }
     }
-    if (!splittable) c.S = 1;
     c.S = std::min(c.S, std::max(1, k_steps / 2));
     // the exchange buffer holds S slices of (padded columns) x (padded rows)
     const size_t slice = (size_t)blocks_of(c) * 4 * c.NT * c.MT * 1024;

@@ -82,11 +82,12 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
         d.p.req_n[t] = n;
         d.p.req_row0[t] = row0;
         if (t == B - 1) d.p.req_row0[B] = s_row0[B];
-        // nodes: parents precede children, so one forward sweep gives depth and ancestor set
+        // trees: parents precede children, so one forward sweep gives depth and ancestor set
+        // (the rows of chains are filled in parallel by plan_fill_kernel)
         unsigned long long anc_prev = 0;
         int depth_prev = -1;
-        for (int i = 0; i < n; ++i) {
-            int par = d.parents ? d.parents[t * a.k_max + i] : i - 1;
+        for (int i = 0; d.parents && i < n; ++i) {
+            int par = d.parents[t * a.k_max + i];
             if (par < -1 || par >= i) { atomicOr(d.err, 2u); par = -1; }
             unsigned long long anc;
             int depth;
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
             else if (par == i - 1) { anc = anc_prev; depth = depth_prev + 1; }
             else { anc = d.p.row_anc[row0 + par]; depth = d.p.row_pos[row0 + par] - P + 1; }
             anc |= 1ull << i;
-            int tok = d.tokens[t * a.k_max + i];
+            int tok = d.tokens[t * a.tok_stride + a.tok_off + i];
             if (tok < 0 || tok >= d.vocab) { atomicOr(d.err, 4u); tok = 0; }
             d.p.row_req[row0 + i] = t;
             d.p.row_node[row0 + i] = i;
@@ -123,11 +124,33 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
     }
 }
 
-// Second half of the plan, one thread per entry: physical page ids of every attention work item
-// (padded with the chunk's last page, so that the attention kernel can load its page ids without
-// knowing the chunk length) and the rotary table (cos, sin)(pos * theta_i), computed in double.
-__global__ __launch_bounds__(256) void plan_fill_kernel(PlanDev d, int n_items, int rows) {
+// Second half of the plan, one thread per entry: the rows of chain blocks (request, node, position,
+// token, cache location), the physical page ids of every attention work item (padded with the
+// chunk's last page, so that the attention kernel can load its page ids without knowing the chunk
+// length) and the rotary table (cos, sin)(pos * theta_i), computed in double.
+__device__ __forceinline__ int find_request(const int32_t *row0, int B, int m) {
+    int lo = 0, hi = B - 1;                                   // largest b with row0[b] <= m
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (row0[mid] <= m) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void plan_fill_kernel(PlanArgs a, PlanDev d, int n_items, int rows) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (!d.parents && idx < rows) {
+        const int b = find_request(d.p.req_row0, a.B, idx), i = idx - d.p.req_row0[b];
+        const int P = d.p.req_P[b], slot = d.p.req_slot[b];
+        int tok = d.tokens[b * a.tok_stride + a.tok_off + i];
+        if (tok < 0 || tok >= d.vocab) { atomicOr(d.err, 4u); tok = 0; }
+        d.p.row_req[idx] = b;
+        d.p.row_node[idx] = i;
+        d.p.row_pos[idx] = P + i;
+        d.p.row_anc[idx] = i < 63 ? (2ull << i) - 1ull : ~0ull;
+        d.p.row_tok[idx] = tok;
+        d.p.row_kvloc[idx] = d.page_table[(size_t)slot * d.max_pages + (P + i) / SEV_PAGE] * SEV_PAGE + (P + i) % SEV_PAGE;
+    }
     if (idx < n_items * SEV_ATT_MAX_CP) {
         const int it = idx / SEV_ATT_MAX_CP, i = idx - it * SEV_ATT_MAX_CP;
         const int4 ia = d.p.it_a[it], ib = d.p.it_b[it];
@@ -136,9 +159,15 @@ __global__ __launch_bounds__(256) void plan_fill_kernel(PlanDev d, int n_items, 
     const int half = d.hd / 2;
     if (idx < rows * half) {
         const int r = idx / half, i = idx - r * half;
+        int pos;
+        if (d.parents) pos = d.p.row_pos[r];                  // written by plan_kernel
+        else {
+            const int b = find_request(d.p.req_row0, a.B, r);
+            pos = d.p.req_P[b] + r - d.p.req_row0[b];
+        }
         const double theta = pow(d.rope_base, -2.0 * (double)i / (double)d.hd);
         double s, c;
-        sincos((double)d.p.row_pos[r] * theta, &s, &c);
+        sincos((double)pos * theta, &s, &c);
         d.p.row_cs[idx] = make_float2((float)c, (float)s);
     }
 }
@@ -161,8 +190,8 @@ void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_toke
     d.page_table = kv->page_table;
     d.max_pages = kv->max_pages_per_req;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(256), 0, st, pa, d);
-    const int64_t entries = std::max<int64_t>((int64_t)n_items * SEV_ATT_MAX_CP, (int64_t)rows * (d.hd / 2));
-    hipLaunchKernelGGL(plan_fill_kernel, dim3((unsigned)((entries + 255) / 256)), dim3(256), 0, st, d, n_items, rows);
+    const int64_t entries = std::max<int64_t>((int64_t)n_items * SEV_ATT_MAX_CP, (int64_t)rows * std::max(1, d.hd / 2));
+    hipLaunchKernelGGL(plan_fill_kernel, dim3((unsigned)((entries + 255) / 256)), dim3(256), 0, st, pa, d, n_items, rows);
 }
 
 // ---------------------------------------------------------------------------
@@ -179,7 +208,7 @@ __global__ void accept_kernel(DevPlan p, int B, int k_max, int mode, const int32
     int32_t *path = pend_path + (size_t)slot * SEV_MAX_DRAFT;
     int a = 0, want;
     if (mode == 1) {                       // append: keep the whole chain
-        for (int i = 0; i < n; ++i) path[i] = i;
+        for (int i = 0; i < n && i < SEV_MAX_DRAFT; ++i) path[i] = i;     // (longer appended blocks are never re-ordered)
         a = n;
         want = row_argmax[row0 + n - 1];
     } else {
@@ -233,6 +262,7 @@ __global__ void commit_copy_kernel(SlotList sl, KvGeom g, const int32_t *page_ta
     const int slot = sl.s[blockIdx.y];
     if (pend_n[slot] == 0) return;
     const int a = pend_a[slot], P = pend_P[slot];
+    if (a > SEV_MAX_DRAFT) return;                       // an appended block longer than any draft: already in place
     const int32_t *path = pend_path + (size_t)slot * SEV_MAX_DRAFT;
     bool moved = false;
     for (int j = 0; j < a; ++j) moved |= (path[j] != j);

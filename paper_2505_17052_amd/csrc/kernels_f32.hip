@@ -116,13 +116,15 @@ __global__ void rope_kv_f32_kernel(float *qkv, DevPlan p, KvGeom g, const int32_
 }
 
 // Masked attention of one (row, query head) per wave over the request's paged cache:
-// all prefix positions, plus the block's nodes that are ancestors-or-self of the row's node.
+// all prefix positions, plus the block's nodes that are ancestors-or-self of the row's node (chains:
+// the nodes up to the row's own, whatever the block length).
 __global__ __launch_bounds__(64) void attn_f32_kernel(const float *qkv, float *out, DevPlan p, KvGeom g,
                                                       const int32_t *page_table, int max_pages, int layer, int Hq,
                                                       int n_qkv, float scale) {
     const int m = blockIdx.x, j = blockIdx.y, lane = threadIdx.x, hd = g.hd;
     const int b = p.row_req[m], P = p.req_P[b], n = p.req_n[b], slot = p.req_slot[b];
     const unsigned long long anc = p.row_anc[m];
+    const int node = p.row_node[m];
     const int h = (j * g.Hkv) / Hq;
     const float *q = qkv + (size_t)m * n_qkv + j * hd;
     const int32_t *pt = page_table + (size_t)slot * max_pages;
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(64) void attn_f32_kernel(const float *qkv, float *o
     for (int r = 0; r < 4; ++r) qv[r] = (lane + 64 * r < hd) ? q[lane + 64 * r] : 0.f;
     float mx = -INFINITY, den = 0.f;
     for (int t = 0; t < P + n; ++t) {
-        if (t >= P && !((anc >> (t - P)) & 1ull)) continue;
+        if (t >= P && (p.causal ? (t - P > node) : !((anc >> (t - P)) & 1ull))) continue;
         const size_t pb = ((size_t)pt[t / SEV_PAGE] * g.Hkv + h) * blk + (size_t)(t % SEV_PAGE) * hd;
         float s = 0.f;
 #pragma unroll

@@ -268,6 +268,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     const size_t o_am = take(rows_pad * 4);
     const size_t o_lg = take(bf ? 4 : rows_pad * (size_t)d.vocab * 4);
     const size_t o_ssq = take(2 * rows_pad * 8);
+    const size_t o_tmp = take(2 * SEV_MAX_BATCH * 4);
     kv->ws_bytes = off;
     hipError_t e = hipMalloc((void **)&kv->ws, kv->ws_bytes);
     if (e != hipSuccess) {
@@ -323,6 +324,8 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->lm_idx = (int32_t *)(w + o_li);
     kv->row_argmax = (int32_t *)(w + o_am);
     kv->logits_f32 = (float *)(w + o_lg);
+    kv->tmp_accept = (int32_t *)(w + o_tmp);
+    kv->tmp_bonus = kv->tmp_accept + SEV_MAX_BATCH;
     kv->ssq[0] = (unsigned long long *)(w + o_ssq);
     kv->ssq[1] = kv->ssq[0] + rows_pad;
     launch_fill_i32(kv->next_tok, -1, max_requests, 0);
@@ -541,28 +544,34 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     }
 }
 
-extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_args *a, void *stream) {
-    if (!m || !kv || !a) return sev_fail(SEV_EINVAL, "null argument");
-    if (kv->model != m) return sev_fail(SEV_EINVAL, "cache was created for another model");
-    if (a->B < 1 || a->B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", a->B, SEV_MAX_BATCH);
-    if (a->k_max < 1 || a->k_max > SEV_MAX_DRAFT) return sev_fail(SEV_EINVAL, "k=%d outside 1..%d", a->k_max, SEV_MAX_DRAFT);
-    if (!a->prefix_lens || !a->draft_tokens || !a->accept_len || !a->bonus_token)
-        return sev_fail(SEV_EINVAL, "prefix_lens, draft_tokens, accept_len and bonus_token are required");
-    if (a->mode != 0 && a->mode != 1) return sev_fail(SEV_EINVAL, "mode must be 0 (verify) or 1 (append)");
-    if (a->mode == 1 && a->parents) return sev_fail(SEV_EINVAL, "append mode takes chains only");
+// One block forward: the shared body of sev_verify_ex and sev_prefill.  The caller has checked the
+// public limits; here: slots, capacity, row budget.
+struct BlockCall {
+    const int32_t *slots, *prefix_lens, *lens;   // host; lens == nullptr: every request has n_all nodes
+    int n_all;
+    const int32_t *tokens;                       // device: node i of request b at tokens[b * tok_stride + tok_off + i]
+    int tok_stride, tok_off;
+    const int32_t *parents;                      // device [B][tok_stride] or nullptr (chains)
+    int B, mode;
+    int32_t *accept_len, *bonus_token, *accept_path, *row_argmax;
+    float *logits;
+};
+
+static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStream_t st) {
     PlanArgs pa;
-    pa.B = a->B;
-    pa.k_max = a->k_max;
-    pa.mode = a->mode;
+    pa.B = c.B;
+    pa.k_max = c.tok_stride;
+    pa.mode = c.mode;
+    pa.tok_stride = c.tok_stride;
+    pa.tok_off = c.tok_off;
     int64_t rows = 0;
-    for (int b = 0; b < a->B; ++b) {
-        const int slot = a->slots ? a->slots[b] : b;
+    for (int b = 0; b < c.B; ++b) {
+        const int slot = c.slots ? c.slots[b] : b;
         if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "request %d: slot %d out of range", b, slot);
-        for (int c = 0; c < b; ++c)
-            if (pa.slot[c] == slot) return sev_fail(SEV_EINVAL, "slot %d listed twice", slot);
-        const int n = a->draft_lens ? a->draft_lens[b] : a->k_max;
-        if (n < 1 || n > a->k_max) return sev_fail(SEV_EINVAL, "request %d: draft length %d outside 1..%d", b, n, a->k_max);
-        const int P = a->prefix_lens[b];
+        for (int e = 0; e < b; ++e)
+            if (pa.slot[e] == slot) return sev_fail(SEV_EINVAL, "slot %d listed twice", slot);
+        const int n = c.lens ? c.lens[b] : c.n_all;
+        const int P = c.prefix_lens[b];
         if (P < 0) return sev_fail(SEV_EINVAL, "request %d: negative prefix length", b);
         if ((int64_t)P + n > (int64_t)kv->host_pages[slot] * SEV_PAGE)
             return sev_fail(SEV_ENOSPACE, "request %d: %d+%d tokens exceed the %d pages of slot %d", b, P, n,
@@ -572,26 +581,111 @@ extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_ar
         pa.nd[b] = n;
         rows += n;
     }
-    if (rows > kv->max_rows) return sev_fail(SEV_ENOSPACE, "%lld draft tokens exceed max_rows=%d", (long long)rows, kv->max_rows);
-    hipStream_t st = (hipStream_t)stream;
+    if (rows > kv->max_rows) return sev_fail(SEV_ENOSPACE, "%lld tokens exceed max_rows=%d", (long long)rows, kv->max_rows);
     int n_items = 0, n_groups = 0, cp = 64;
     bool att_direct = false;
     if (m->d.dtype == SEV_BF16) {
         cp = pick_chunk_pages(kv, pa, &n_items, &n_groups, &att_direct);
         if (cp < 0) return sev_fail(SEV_ENOSPACE, "attention work list does not fit");
     }
+    kv->plan.causal = c.parents ? 0 : 1;
     {
         Prof p(kv, st, PROF_OTHER);
-        launch_plan(kv, pa, a->draft_tokens, a->parents, (int)rows, cp, n_items, st);
+        launch_plan(kv, pa, c.tokens, c.parents, (int)rows, cp, n_items, st);
     }
-    if (m->d.dtype == SEV_F32) f32_forward(m, kv, (int)rows, a->B, a->logits, st);
-    else bf16_forward(m, kv, (int)rows, a->B, n_items, n_groups, att_direct, a->logits, st);
+    if (m->d.dtype == SEV_F32) f32_forward(m, kv, (int)rows, c.B, c.logits, st);
+    else bf16_forward(m, kv, (int)rows, c.B, n_items, n_groups, att_direct, c.logits, st);
     {
         Prof p(kv, st, PROF_OTHER);
-        launch_accept(kv, a->B, a->k_max, a->mode, a->draft_tokens, a->parents, a->accept_len, a->bonus_token,
-                      a->accept_path, st);
-        if (a->row_argmax)
-            SEV_HIP(hipMemcpyAsync(a->row_argmax, kv->row_argmax, (size_t)rows * 4, hipMemcpyDeviceToDevice, st));
+        launch_accept(kv, c.B, c.tok_stride, c.mode, c.tokens, c.parents, c.accept_len, c.bonus_token, c.accept_path, st);
+        if (c.row_argmax)
+            SEV_HIP(hipMemcpyAsync(c.row_argmax, kv->row_argmax, (size_t)rows * 4, hipMemcpyDeviceToDevice, st));
+    }
+    SEV_HIP(hipGetLastError());
+    return SEV_OK;
+}
+
+extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_args *a, void *stream) {
+    if (!m || !kv || !a) return sev_fail(SEV_EINVAL, "null argument");
+    if (kv->model != m) return sev_fail(SEV_EINVAL, "cache was created for another model");
+    if (a->B < 1 || a->B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", a->B, SEV_MAX_BATCH);
+    if (a->k_max < 1 || a->k_max > SEV_MAX_DRAFT) return sev_fail(SEV_EINVAL, "k=%d outside 1..%d", a->k_max, SEV_MAX_DRAFT);
+    if (!a->prefix_lens || !a->draft_tokens || !a->accept_len || !a->bonus_token)
+        return sev_fail(SEV_EINVAL, "prefix_lens, draft_tokens, accept_len and bonus_token are required");
+    if (a->mode != 0 && a->mode != 1) return sev_fail(SEV_EINVAL, "mode must be 0 (verify) or 1 (append)");
+    if (a->mode == 1 && a->parents) return sev_fail(SEV_EINVAL, "append mode takes chains only");
+    if (a->draft_lens)
+        for (int b = 0; b < a->B; ++b)
+            if (a->draft_lens[b] < 1 || a->draft_lens[b] > a->k_max)
+                return sev_fail(SEV_EINVAL, "request %d: draft length %d outside 1..%d", b, a->draft_lens[b], a->k_max);
+    BlockCall c;
+    memset(&c, 0, sizeof(c));
+    c.slots = a->slots; c.prefix_lens = a->prefix_lens; c.lens = a->draft_lens; c.n_all = a->k_max;
+    c.tokens = a->draft_tokens; c.tok_stride = a->k_max; c.tok_off = 0; c.parents = a->parents;
+    c.B = a->B; c.mode = a->mode;
+    c.accept_len = a->accept_len; c.bonus_token = a->bonus_token; c.accept_path = a->accept_path;
+    c.row_argmax = a->row_argmax; c.logits = a->logits;
+    return run_block(m, kv, c, (hipStream_t)stream);
+}
+
+// Prefill: long chains are fed through the same forward pass in chunks that fit the row budget, each
+// chunk appended (all tokens kept) and committed before the next one starts.
+extern "C" int sev_prefill(const sev_model *m, sev_kv *kv, const int32_t *slots, const int32_t *start_lens,
+                           const int32_t *n_tokens, const int32_t *tokens, int B, int t_max, void *stream) {
+    if (!m || !kv) return sev_fail(SEV_EINVAL, "null argument");
+    if (kv->model != m) return sev_fail(SEV_EINVAL, "cache was created for another model");
+    if (B < 1 || B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", B, SEV_MAX_BATCH);
+    if (!start_lens || !n_tokens || !tokens || t_max < 1) return sev_fail(SEV_EINVAL, "start_lens, n_tokens and tokens are required");
+    int64_t longest = 0;
+    for (int b = 0; b < B; ++b) {
+        if (n_tokens[b] < 1 || n_tokens[b] > t_max) return sev_fail(SEV_EINVAL, "request %d: %d tokens outside 1..%d", b, n_tokens[b], t_max);
+        const int slot = slots ? slots[b] : b;
+        if (slot < 0 || slot >= kv->max_req) return sev_fail(SEV_EINVAL, "request %d: slot %d out of range", b, slot);
+        if (start_lens[b] < 0 || (int64_t)start_lens[b] + n_tokens[b] > (int64_t)kv->host_pages[slot] * SEV_PAGE)
+            return sev_fail(SEV_ENOSPACE, "request %d: %d+%d tokens exceed the %d pages of slot %d", b, start_lens[b], n_tokens[b],
+                            kv->host_pages[slot], slot);
+        longest = std::max<int64_t>(longest, n_tokens[b]);
+    }
+    hipStream_t st = (hipStream_t)stream;
+    // chunk length: all still-active requests advance together; rows of a chunk fit max_rows, and a request's
+    // rows per chunk stay moderate so that the attention work list fits
+    int32_t sl[SEV_MAX_BATCH], pre[SEV_MAX_BATCH], len[SEV_MAX_BATCH], idx[SEV_MAX_BATCH];
+    for (int64_t done = 0; done < longest;) {
+        int act = 0;
+        for (int b = 0; b < B; ++b)
+            if (n_tokens[b] > done) idx[act++] = b;
+        const int64_t ch = std::max<int64_t>(1, std::min<int64_t>(512, kv->max_rows / act));
+        for (int r = 0; r < act; ++r) {
+            const int b = idx[r];
+            sl[r] = slots ? slots[b] : b;
+            pre[r] = start_lens[b] + (int32_t)done;
+            len[r] = (int32_t)std::min<int64_t>(ch, n_tokens[b] - done);
+        }
+        // the chunk's rows must be contiguous per request in the token array: request r reads row idx[r] of tokens.
+        // Requests that have finished leave holes in the batch, so each active request is issued with its own row.
+        // (B is small on this path; one block call per chunk covers all requests when none has finished.)
+        bool dense = (act == B);
+        if (dense) {
+            BlockCall c;
+            memset(&c, 0, sizeof(c));
+            c.slots = sl; c.prefix_lens = pre; c.lens = len; c.tokens = tokens; c.tok_stride = t_max; c.tok_off = (int)done;
+            c.B = act; c.mode = 1; c.accept_len = kv->tmp_accept; c.bonus_token = kv->tmp_bonus;
+            const int rc = run_block(m, kv, c, st);
+            if (rc != SEV_OK) return rc;
+            launch_commit(kv, sl, act, false, st);
+        } else {
+            for (int r = 0; r < act; ++r) {
+                BlockCall c;
+                memset(&c, 0, sizeof(c));
+                c.slots = sl + r; c.prefix_lens = pre + r; c.lens = len + r;
+                c.tokens = tokens + (size_t)idx[r] * t_max; c.tok_stride = t_max; c.tok_off = (int)done;
+                c.B = 1; c.mode = 1; c.accept_len = kv->tmp_accept; c.bonus_token = kv->tmp_bonus;
+                const int rc = run_block(m, kv, c, st);
+                if (rc != SEV_OK) return rc;
+                launch_commit(kv, sl + r, 1, false, st);
+            }
+        }
+        done += ch;
     }
     SEV_HIP(hipGetLastError());
     return SEV_OK;

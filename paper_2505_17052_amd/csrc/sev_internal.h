@@ -53,6 +53,7 @@ struct sev_model {
 // Per-call description handed to the plan kernel by value.
 struct PlanArgs {
     int B, k_max, mode;
+    int tok_stride, tok_off;  // token of node i of request b: tokens[b * tok_stride + tok_off + i]
     int32_t slot[SEV_MAX_BATCH];
     int32_t prefix[SEV_MAX_BATCH];
     int32_t nd[SEV_MAX_BATCH];
@@ -72,6 +73,7 @@ struct DevPlan {
     int4 *it_a, *it_b;
     int32_t *it_pages;
     int32_t *mg_req, *mg_rg, *mg_item0, *mg_count;         // [merge groups]
+    int causal;               // 1: blocks are chains (node i sees nodes <= i; any length), 0: trees (ancestor masks, <= 64 nodes)
 };
 
 enum ProfClass { PROF_GEMM_QKV = 0, PROF_GEMM_O, PROF_GEMM_GU, PROF_GEMM_DOWN, PROF_GEMM_LM, PROF_ATTN, PROF_OTHER, PROF_N };
@@ -116,6 +118,7 @@ struct sev_kv {
     float *lm_val;            // [tiles][rows] partial arg-max values
     int32_t *lm_idx;
     int32_t *row_argmax;      // [rows]
+    int32_t *tmp_accept, *tmp_bonus;         // [SEV_MAX_BATCH] outputs of internal block runs (prefill)
     float *logits_f32;        // f32 path only: [rows][vocab]
 
     // host mirrors

@@ -81,6 +81,19 @@ class Batch:
                 self.lens[slots[i]] += ns[r]
         torch.cuda.synchronize()
 
+    def prefill(self, token_lists, slots=None):
+        """sev_prefill over whole token lists (any length the slots' pages can hold)."""
+        slots = list(range(self.B)) if slots is None else list(slots)
+        ns = [len(t) for t in token_lists]
+        toks = np.zeros((len(slots), max(ns)), dtype=np.int32)
+        for r, t in enumerate(token_lists):
+            toks[r, :ns[r]] = np.asarray(t, dtype=np.int32)
+        sev.prefill(self.model, self.kv, [self.lens[s] for s in slots], ns, torch.from_numpy(toks).to(self.model.device),
+                    slots=slots)
+        for r, s_ in enumerate(slots):
+            self.lens[s_] += ns[r]
+        torch.cuda.synchronize()
+
     def fill_synthetic(self, seed: int, prefix_lens, last_tokens):
         """Drawn K/V for positions 0..P-2 of every slot, then a real forward over the last prefix
         token so that position P-1 and next_tok come from the model."""
