@@ -417,3 +417,98 @@ def commit(model: Model, cache: Cache) -> None:
 def rollback(cache: Cache) -> None:
     """Discard the pending draft block; length and next_tok stay as they were."""
     cache.pending = None
+
+
+# ---------------------------------------------------------------------------
+# stochastic verification (chains): the distribution-preserving rule
+# ---------------------------------------------------------------------------
+# The paper states that the draft/verify cycle preserves the server model's output
+# distribution exactly (section 4.1, citing speculative sampling) and runs every model at
+# temperature 0.7 (section 5, setup).  The rule of that cited method, written out:
+#   a candidate x drawn by the edge from its distribution q is accepted with probability
+#   min(1, p(x)/q(x)), p being the server's distribution for that position; at the first
+#   rejection the server emits a token drawn from the normalised residual max(0, p - q);
+#   if every candidate is accepted it emits one more token drawn from p.
+# Conventions of this build (readings; the paper does not spell them out): the first
+# candidate of a block is the token the server itself emitted in the previous step
+# (`next_tok`), which has no K/V yet; it is accepted iff it equals next_tok and no random
+# number is spent on it.  Candidate i >= 1 is judged with the server distribution computed
+# at candidate i-1.  All random numbers are inputs: u_acc[i] decides candidate i
+# (accept iff u_acc[i] * q_i(x_i) < p_{i-1}(x_i)), u_emit picks the emitted token by inverse
+# CDF in token-id order.
+
+
+def softmax_t(logits: np.ndarray, temperature: float) -> np.ndarray:
+    z = np.asarray(logits, dtype=np.float64) / float(temperature)
+    z = z - z.max()
+    e = np.exp(z)
+    return e / e.sum()
+
+
+def inverse_cdf(weights: np.ndarray, u: float):
+    """Index i with cum[i-1] <= u * total < cum[i] (token-id order), and the distance of u * total to
+    the nearest boundary of that cell, relative to the total (how firm the draw is)."""
+    w = np.asarray(weights, dtype=np.float64)
+    cum = np.cumsum(w)
+    total = cum[-1]
+    t = u * total
+    i = int(np.searchsorted(cum, t, side="right"))
+    i = min(i, len(w) - 1)
+    while w[i] == 0.0 and i > 0:          # u * total == a boundary shared with empty cells
+        i -= 1
+    lo = cum[i] - w[i]
+    margin = min(t - lo, cum[i] - t) / total if total > 0 else 0.0
+    return i, float(margin)
+
+
+@dataclass
+class SampleResult:
+    accept_len: int
+    emitted: int               # the one additional token (resampled at a rejection, or drawn from p after full acceptance)
+    accept_margin: float       # smallest |u*q - p| / max(p, u*q) over the decisions taken (how firm they were)
+    emit_margin: float         # see inverse_cdf
+    logits: np.ndarray
+
+
+def accept_sample_chain(draft: np.ndarray, next_tok: int, p_rows: np.ndarray, q_rows: np.ndarray,
+                        u_acc: np.ndarray, u_emit: float):
+    """p_rows[i] = server distribution after candidate i; q_rows[i] = edge distribution candidate i was
+    drawn from (q_rows[0] is unused: candidate 0 is the server's own previous token)."""
+    n = len(draft)
+    if int(draft[0]) != int(next_tok):
+        # the edge is out of step with the server: nothing can be accepted; the server re-sends its token
+        return 0, int(next_tok), 1.0, 1.0
+    a, margin = 1, 1.0
+    for i in range(1, n):
+        x = int(draft[i])
+        p, q = float(p_rows[i - 1][x]), float(q_rows[i][x])
+        lhs = float(u_acc[i]) * q
+        margin = min(margin, abs(lhs - p) / max(p, lhs, 1e-300))
+        if lhs < p:
+            a += 1
+        else:
+            res = np.maximum(p_rows[i - 1] - q_rows[i], 0.0)
+            if res.sum() <= 0.0:           # p == q everywhere: a rejection has probability zero; fall back to p
+                res = p_rows[i - 1]
+            tok, em = inverse_cdf(res, u_emit)
+            return a, tok, margin, em
+    tok, em = inverse_cdf(p_rows[n - 1], u_emit)
+    return a, tok, margin, em
+
+
+def verify_sample(model: Model, caches: Sequence[Cache], drafts: Sequence[np.ndarray], q_rows: Sequence[np.ndarray],
+                  u_acc: Sequence[np.ndarray], u_emit: Sequence[float], temperature: float) -> List[SampleResult]:
+    """Batched stochastic verification of chains: one forward over every request's block, then the
+    accept / resample rule above.  Leaves each cache PENDING with the accepted prefix and the emitted
+    token as its next token."""
+    R = len(caches)
+    pars = [chain_parents(len(d)) for d in drafts]
+    logits, nk, nv = forward_blocks(model, caches, drafts, pars)
+    res = []
+    for r, c in enumerate(caches):
+        p_rows = np.stack([softmax_t(row, temperature) for row in logits[r]])
+        a, tok, m1, m2 = accept_sample_chain(np.asarray(drafts[r]), c.next_tok, p_rows, np.asarray(q_rows[r], dtype=np.float64),
+                                             np.asarray(u_acc[r]), float(u_emit[r]))
+        c.pending = Pending(nk[r], nv[r], list(range(a)), tok)
+        res.append(SampleResult(a, tok, m1, m2, logits[r]))
+    return res

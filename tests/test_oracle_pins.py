@@ -472,3 +472,92 @@ def test_workload_chain_recipe(model):
     r = vo.verify(m, [c], [d])[0]
     first_bad = next((j for j in range(4) if d[j] != g[j]), 4)
     assert r.accept_len == first_bad and r.bonus_token == g[first_bad]
+
+
+# ---------------------------------------------------------------------------
+# stochastic verification (paper section 4.1: the cycle preserves the server model's output
+# distribution; section 5: temperature 0.7).  The oracle's rule is pinned by what defines it:
+# the emitted tokens must follow the server distribution whatever the edge distribution is.
+# ---------------------------------------------------------------------------
+def _one_step(p, q, x, ua, ue):
+    """Block [server's previous token, x]: returns the first NEW token of the output stream."""
+    acc, tok, _, _ = vo.accept_sample_chain(np.array([0, x]), 0, np.stack([p, p]), np.stack([q, q]), np.array([0.0, ua]), ue)
+    return (x if acc == 2 else tok), acc
+
+
+def test_stochastic_rule_preserves_the_server_distribution():
+    rng = np.random.default_rng(5)
+    V, N = 7, 120000
+    p = rng.dirichlet(np.ones(V) * 0.7)
+    q = rng.dirichlet(np.ones(V) * 0.7)
+    q[2] = 0.0; q /= q.sum()                              # a token the edge never proposes
+    xs = rng.choice(V, size=N, p=q)
+    ua, ue = rng.random(N), rng.random(N)
+    cnt, n_acc = np.zeros(V), 0
+    for x, a, e in zip(xs, ua, ue):
+        t, acc = _one_step(p, q, int(x), a, e)
+        cnt[t] += 1
+        n_acc += acc == 2
+    sigma = np.sqrt(p * (1 - p) / N)
+    assert np.all(np.abs(cnt / N - p) < 5 * sigma + 1e-4), (cnt / N, p)
+    # acceptance probability has the closed form sum_x min(p, q)
+    want = np.minimum(p, q).sum()
+    assert abs(n_acc / N - want) < 5 * np.sqrt(want * (1 - want) / N)
+
+
+def test_stochastic_rule_special_cases_and_greedy_limit():
+    p = np.array([0.1, 0.6, 0.3])
+    # identical distributions: every proposal is accepted, whatever the random number
+    for x in range(3):
+        for u in (0.0, 0.5, 0.999999):
+            assert _one_step(p, p, x, u, 0.3)[1] == 2
+    # the edge proposes a token the server gives probability zero: always rejected, emitted token ~ p
+    p0 = np.array([0.0, 0.7, 0.3]); q0 = np.array([1.0, 0.0, 0.0])
+    assert _one_step(p0, q0, 0, 0.0, 0.69)[0] == 1 and _one_step(p0, q0, 0, 0.0, 0.71)[0] == 2
+    # temperature -> 0: one-hot server distribution = the greedy rule (accept iff the proposal is the arg-max)
+    logits = np.array([0.3, 2.0, -1.0, 1.9])
+    hot = vo.softmax_t(logits, 1e-4)
+    assert hot.argmax() == 1 and hot[1] > 1 - 1e-12
+    qh = np.array([0.25, 0.25, 0.25, 0.25])
+    assert _one_step(hot, qh, 1, 0.999, 0.5) == (1, 2)
+    assert _one_step(hot, qh, 3, 0.0001, 0.5) == (1, 1)    # rejected, and the replacement is the arg-max
+    # the first candidate is the server's own previous token: a mismatch accepts nothing and returns that token
+    a, tok, _, _ = vo.accept_sample_chain(np.array([4, 1]), 2, np.stack([p, p]), np.stack([p, p]), np.array([0.0, 0.1]), 0.5)
+    assert (a, tok) == (0, 2)
+    # softmax with temperature: ratios of probabilities follow exp(delta / T)
+    pr = vo.softmax_t(np.array([1.0, 0.3]), 0.7)
+    assert abs(pr[0] / pr[1] - np.exp(0.7 / 0.7)) < 1e-12 and abs(pr.sum() - 1) < 1e-15
+
+
+def test_inverse_cdf_hand_cases():
+    w = np.array([0.2, 0.0, 0.5, 0.3])
+    assert vo.inverse_cdf(w, 0.0)[0] == 0 and vo.inverse_cdf(w, 0.19)[0] == 0
+    assert vo.inverse_cdf(w, 0.21)[0] == 2 and vo.inverse_cdf(w, 0.69)[0] == 2 and vo.inverse_cdf(w, 0.71)[0] == 3
+    i, m = vo.inverse_cdf(w * 4.0, 0.45)                   # unnormalised weights; 0.45 sits 0.25 inside cell [0.2, 0.7)
+    assert i == 2 and abs(m - 0.25) < 1e-12
+
+
+def test_stochastic_chain_two_steps_follow_the_joint_distribution():
+    """Two judged candidates with position-dependent tables: the first two NEW tokens of the stream must be
+    distributed as p1(a) * p2(b | a), the server's own two-step sampling."""
+    rng = np.random.default_rng(9)
+    V, N = 3, 60000
+    p1 = rng.dirichlet(np.ones(V)); q1 = rng.dirichlet(np.ones(V))
+    p2 = rng.dirichlet(np.ones(V), size=V); q2 = rng.dirichlet(np.ones(V), size=V)      # rows: conditional on the first token
+    joint = np.zeros((V, V))
+    for _ in range(N):
+        x1 = rng.choice(V, p=q1); x2 = rng.choice(V, p=q2[x1])
+        u = rng.random(3); ue = rng.random(2)
+        # server rows: after candidate 0 -> p1; after candidate 1 (= x1) -> p2[x1]; after candidate 2 unused here
+        a, tok, _, _ = vo.accept_sample_chain(np.array([0, x1, x2]), 0, np.stack([p1, p2[x1], p1]), np.stack([q1, q1, q2[x1]]),
+                                              u, ue[0])
+        if a == 3:
+            t1, t2 = x1, x2
+        elif a == 2:
+            t1, t2 = x1, tok                               # x2 rejected: tok ~ residual of p2[x1]
+        else:
+            t1 = tok                                       # x1 rejected: next round starts from t1; its first new token ~ p2[t1]
+            t2 = rng.choice(V, p=p2[t1])
+        joint[t1, t2] += 1
+    want = p1[:, None] * p2
+    assert np.max(np.abs(joint / N - want)) < 5 * np.sqrt(0.25 / N)
