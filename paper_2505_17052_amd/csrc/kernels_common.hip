@@ -297,6 +297,145 @@ __global__ void commit_state_kernel(SlotList sl, int B, int rollback, int32_t *s
     pend_n[slot] = 0;
 }
 
+// ---------------------------------------------------------------------------
+// stochastic verification of chains (paper section 4.1: the draft/verify cycle preserves the
+// server model's output distribution, by the accept / resample rule of speculative sampling;
+// section 5: temperature 0.7).  All random numbers are inputs.
+//
+// softmax_stats_kernel: one block per row: the row's largest logit and the sum of
+//   exp((logit - max) / T).
+// sample_accept_kernel: one block per request.  Thread 0 walks the chain: candidate 0 must be the
+//   server's own previous token; candidate i >= 1 is accepted iff u_acc[i] * q_i(x_i) < p_{i-1}(x_i).
+//   Then the whole block draws the emitted token by inverse CDF in token-id order from the
+//   residual max(0, p - q) at the first rejection (p itself after full acceptance, or when the
+//   residual is empty): every thread sums a contiguous range of ids, the ranges are scanned in
+//   order, and the thread whose range holds u * total walks it.  Same order every run.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void softmax_stats_kernel(const float *logits, int vocab, float inv_t, float2 *stats) {
+    __shared__ float red[16];
+    const float *row = logits + (size_t)blockIdx.x * vocab;
+    float mx = -INFINITY;
+    for (int v = threadIdx.x; v < vocab; v += 1024) mx = fmaxf(mx, row[v]);
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = red[0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
+    __syncthreads();
+    float sum = 0.f;
+    for (int v = threadIdx.x; v < vocab; v += 1024) sum += expf((row[v] - mx) * inv_t);
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float z = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) z += red[w];
+        stats[blockIdx.x] = make_float2(mx, z);
+    }
+}
+
+__global__ __launch_bounds__(1024) void sample_accept_kernel(DevPlan p, int k_max, const int32_t *tokens, const float *logits,
+                                                             const float *draft_probs, const float2 *stats, int vocab, float inv_t,
+                                                             const float *u_acc, const float *u_emit, const int32_t *next_tok,
+                                                             int32_t *pend_n, int32_t *pend_a, int32_t *pend_bonus, int32_t *pend_path,
+                                                             int32_t *accept_len, int32_t *emitted) {
+    __shared__ int s_a, s_rej;
+    __shared__ float s_part[1024], s_partp[1024];
+    __shared__ float s_total, s_totalp;
+    const int b = blockIdx.x, t = threadIdx.x;
+    const int slot = p.req_slot[b], n = p.req_n[b], row0 = p.req_row0[b];
+    if (t == 0) {
+        int a = 0, rej = 0;
+        if (tokens[b * k_max] == next_tok[slot]) {
+            a = 1;
+            for (int i = 1; i < n; ++i) {
+                const int x = tokens[b * k_max + i];
+                const float2 st = stats[row0 + i - 1];
+                const float pr = expf((logits[(size_t)(row0 + i - 1) * vocab + x] - st.x) * inv_t) / st.y;
+                const float q = draft_probs[(size_t)(row0 + i) * vocab + x];
+                if (u_acc[b * k_max + i] * q < pr) ++a;
+                else { rej = 1; break; }
+            }
+        }
+        s_a = a;
+        s_rej = rej;
+    }
+    __syncthreads();
+    const int a = s_a, rej = s_rej;
+    int tok = next_tok[slot];
+    if (a > 0) {
+        // weights over token ids: residual of (p after candidate a-1) against (q of candidate a), and p itself
+        const float *lrow = logits + (size_t)(row0 + a - 1) * vocab;
+        const float *qrow = draft_probs + (size_t)(row0 + (rej ? a : a - 1)) * vocab;     // unused without a rejection
+        const float2 st = stats[row0 + a - 1];
+        const float inv_z = 1.0f / st.y;
+        const int per = (vocab + 1023) / 1024, v0 = t * per, v1 = min(vocab, v0 + per);
+        float sr = 0.f, sp = 0.f;
+        for (int v = v0; v < v1; ++v) {
+            const float pv = expf((lrow[v] - st.x) * inv_t) * inv_z;
+            sp += pv;
+            if (rej) sr += fmaxf(pv - qrow[v], 0.f);
+        }
+        s_part[t] = sr;
+        s_partp[t] = sp;
+        __syncthreads();
+        if (t == 0) {
+            float tr = 0.f, tp = 0.f;
+            for (int i = 0; i < 1024; ++i) { tr += s_part[i]; tp += s_partp[i]; }
+            s_total = tr;
+            s_totalp = tp;
+        }
+        __syncthreads();
+        const bool use_res = rej && s_total > 0.f;
+        const float total = use_res ? s_total : s_totalp;
+        const float target = u_emit[b] * total;
+        // thread 0 finds the range that holds the target (ranges in id order), then walks it
+        if (t == 0) {
+            const float *part = use_res ? s_part : s_partp;
+            float cum = 0.f;
+            int seg = 1023;
+            for (int i = 0; i < 1024; ++i) {
+                if (target < cum + part[i]) { seg = i; break; }
+                cum += part[i];
+            }
+            const int w0 = seg * per, w1 = min(vocab, w0 + per);
+            int pick = -1, last_nonzero = -1;
+            for (int v = w0; v < w1; ++v) {
+                const float pv = expf((lrow[v] - st.x) * inv_t) * inv_z;
+                const float w = use_res ? fmaxf(pv - qrow[v], 0.f) : pv;
+                if (w > 0.f) last_nonzero = v;
+                if (target < cum + w) { pick = v; break; }
+                cum += w;
+            }
+            if (pick < 0) pick = last_nonzero >= 0 ? last_nonzero : max(w0, 0);     // rounding at the very end of the range
+            s_a = pick;
+        }
+        __syncthreads();
+        tok = s_a;
+    }
+    if (t == 0) {
+        int32_t *path = pend_path + (size_t)slot * SEV_MAX_DRAFT;
+        for (int i = 0; i < SEV_MAX_DRAFT; ++i) path[i] = i < a ? i : -1;
+        pend_n[slot] = n;
+        pend_a[slot] = a;
+        pend_bonus[slot] = tok;
+        accept_len[b] = a;
+        emitted[b] = tok;
+    }
+}
+
+void launch_sample(const sev_kv *kv, int B, int k_max, int rows, const int32_t *tokens, const float *logits, const float *draft_probs,
+                   float2 *stats, float temperature, const float *u_acc, const float *u_emit, int32_t *accept_len, int32_t *emitted,
+                   hipStream_t st) {
+    const int vocab = kv->model->d.vocab;
+    const float inv_t = 1.0f / temperature;
+    hipLaunchKernelGGL(softmax_stats_kernel, dim3(rows), dim3(1024), 0, st, logits, vocab, inv_t, stats);
+    hipLaunchKernelGGL(sample_accept_kernel, dim3(B), dim3(1024), 0, st, kv->plan, k_max, tokens, logits, draft_probs, stats, vocab, inv_t,
+                       u_acc, u_emit, kv->next_tok, kv->pend_n, kv->pend_a, kv->pend_bonus, kv->pend_path, accept_len, emitted);
+}
+
 KvGeom sev_kv_geom(const sev_kv *kv);
 
 void launch_commit(const sev_kv *kv, const int32_t *slots, int B, bool rollback, hipStream_t st) {

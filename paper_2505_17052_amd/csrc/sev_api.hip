@@ -269,6 +269,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     const size_t o_lg = take(bf ? 4 : rows_pad * (size_t)d.vocab * 4);
     const size_t o_ssq = take(2 * rows_pad * 8);
     const size_t o_tmp = take(2 * SEV_MAX_BATCH * 4);
+    const size_t o_rst = take(rows_pad * 8);
     kv->ws_bytes = off;
     hipError_t e = hipMalloc((void **)&kv->ws, kv->ws_bytes);
     if (e != hipSuccess) {
@@ -324,6 +325,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->lm_idx = (int32_t *)(w + o_li);
     kv->row_argmax = (int32_t *)(w + o_am);
     kv->logits_f32 = (float *)(w + o_lg);
+    kv->row_stats = (float2 *)(w + o_rst);
     kv->tmp_accept = (int32_t *)(w + o_tmp);
     kv->tmp_bonus = kv->tmp_accept + SEV_MAX_BATCH;
     kv->ssq[0] = (unsigned long long *)(w + o_ssq);
@@ -555,6 +557,9 @@ struct BlockCall {
     int B, mode;
     int32_t *accept_len, *bonus_token, *accept_path, *row_argmax;
     float *logits;
+    // stochastic rule (chains): set draft_probs to switch from greedy acceptance to accept / resample
+    const float *draft_probs, *u_accept, *u_emit;
+    float temperature;
 };
 
 static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStream_t st) {
@@ -597,7 +602,11 @@ static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStre
     else bf16_forward(m, kv, (int)rows, c.B, n_items, n_groups, att_direct, c.logits, st);
     {
         Prof p(kv, st, PROF_OTHER);
-        launch_accept(kv, c.B, c.tok_stride, c.mode, c.tokens, c.parents, c.accept_len, c.bonus_token, c.accept_path, st);
+        if (c.draft_probs)
+            launch_sample(kv, c.B, c.tok_stride, (int)rows, c.tokens, c.logits, c.draft_probs, kv->row_stats, c.temperature, c.u_accept,
+                          c.u_emit, c.accept_len, c.bonus_token, st);
+        else
+            launch_accept(kv, c.B, c.tok_stride, c.mode, c.tokens, c.parents, c.accept_len, c.bonus_token, c.accept_path, st);
         if (c.row_argmax)
             SEV_HIP(hipMemcpyAsync(c.row_argmax, kv->row_argmax, (size_t)rows * 4, hipMemcpyDeviceToDevice, st));
     }
@@ -625,6 +634,29 @@ extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_ar
     c.B = a->B; c.mode = a->mode;
     c.accept_len = a->accept_len; c.bonus_token = a->bonus_token; c.accept_path = a->accept_path;
     c.row_argmax = a->row_argmax; c.logits = a->logits;
+    return run_block(m, kv, c, (hipStream_t)stream);
+}
+
+extern "C" int sev_verify_sample(const sev_model *m, sev_kv *kv, const sev_sample_args *a, void *stream) {
+    if (!m || !kv || !a) return sev_fail(SEV_EINVAL, "null argument");
+    if (kv->model != m) return sev_fail(SEV_EINVAL, "cache was created for another model");
+    if (a->B < 1 || a->B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", a->B, SEV_MAX_BATCH);
+    if (a->k_max < 1 || a->k_max > SEV_MAX_DRAFT) return sev_fail(SEV_EINVAL, "k=%d outside 1..%d", a->k_max, SEV_MAX_DRAFT);
+    if (!a->prefix_lens || !a->draft_tokens || !a->draft_probs || !a->u_accept || !a->u_emit || !a->logits_ws || !a->accept_len ||
+        !a->emitted_token)
+        return sev_fail(SEV_EINVAL, "prefix_lens, draft_tokens, draft_probs, u_accept, u_emit, logits_ws, accept_len and emitted_token are required");
+    if (!(a->temperature > 0.0f) || !(a->temperature < 1e4f)) return sev_fail(SEV_EINVAL, "temperature must be positive");
+    if (a->draft_lens)
+        for (int b = 0; b < a->B; ++b)
+            if (a->draft_lens[b] < 1 || a->draft_lens[b] > a->k_max)
+                return sev_fail(SEV_EINVAL, "request %d: draft length %d outside 1..%d", b, a->draft_lens[b], a->k_max);
+    BlockCall c;
+    memset(&c, 0, sizeof(c));
+    c.slots = a->slots; c.prefix_lens = a->prefix_lens; c.lens = a->draft_lens; c.n_all = a->k_max;
+    c.tokens = a->draft_tokens; c.tok_stride = a->k_max; c.tok_off = 0;
+    c.B = a->B; c.mode = 0;
+    c.accept_len = a->accept_len; c.bonus_token = a->emitted_token; c.logits = a->logits_ws;
+    c.draft_probs = a->draft_probs; c.u_accept = a->u_accept; c.u_emit = a->u_emit; c.temperature = a->temperature;
     return run_block(m, kv, c, (hipStream_t)stream);
 }
 
