@@ -512,3 +512,63 @@ def verify_sample(model: Model, caches: Sequence[Cache], drafts: Sequence[np.nda
         c.pending = Pending(nk[r], nv[r], list(range(a)), tok)
         res.append(SampleResult(a, tok, m1, m2, logits[r]))
     return res
+
+
+# Trees under the stochastic rule (multi-step speculative sampling, the tree generalisation used by the
+# tree-based methods the paper builds on, section 2): at the current node the children are tried in
+# index order; child c with token x, drawn by the edge from q_c, is accepted with probability
+# min(1, p(x)/q_c(x)), p being the CURRENT server distribution at that node; a rejection replaces p by
+# the normalised residual max(0, p - q_c) before the next sibling is tried; when a child is accepted
+# the walk moves there and p becomes the server distribution computed at that child; when no child is
+# left the emitted token is drawn from the current p.  The rule preserves the server distribution when
+# the siblings of a node are independent draws from the same q.  Readings as for chains: the block's
+# root is the token the server emitted in the previous step (a node with parent -1 whose token equals
+# next_tok, lowest index first; without one nothing is accepted).
+
+
+def accept_sample_tree(draft: np.ndarray, parents: np.ndarray, next_tok: int, p_rows: np.ndarray, q_rows: np.ndarray,
+                       u_acc: np.ndarray, u_emit: float):
+    n = len(draft)
+    roots = [c for c in range(n) if parents[c] == -1 and int(draft[c]) == int(next_tok)]
+    if not roots:
+        return 0, int(next_tok), [], 1.0, 1.0
+    cur = roots[0]
+    path, margin = [cur], 1.0
+    p = np.asarray(p_rows[cur], dtype=np.float64)
+    while True:
+        moved = False
+        for c in range(cur + 1, n):
+            if parents[c] != cur:
+                continue
+            x = int(draft[c])
+            px, qx = float(p[x]), float(q_rows[c][x])
+            lhs = float(u_acc[c]) * qx
+            margin = min(margin, abs(lhs - px) / max(px, lhs, 1e-300))
+            if lhs < px:
+                cur = c
+                path.append(c)
+                p = np.asarray(p_rows[c], dtype=np.float64)
+                moved = True
+                break
+            res = np.maximum(p - q_rows[c], 0.0)
+            if res.sum() > 0.0:
+                p = res / res.sum()
+        if not moved:
+            tok, em = inverse_cdf(p, u_emit)
+            return len(path), tok, path, margin, em
+
+
+def verify_sample_tree(model: Model, caches: Sequence[Cache], drafts: Sequence[np.ndarray], parents: Sequence[np.ndarray],
+                       q_rows: Sequence[np.ndarray], u_acc: Sequence[np.ndarray], u_emit: Sequence[float], temperature: float):
+    """Batched stochastic verification of trees; returns (SampleResult, path) per request and leaves the
+    caches PENDING with the accepted path."""
+    pars = [np.asarray(p, dtype=np.int64) for p in parents]
+    logits, nk, nv = forward_blocks(model, caches, drafts, pars)
+    out = []
+    for r, c in enumerate(caches):
+        p_rows = np.stack([softmax_t(row, temperature) for row in logits[r]])
+        a, tok, path, m1, m2 = accept_sample_tree(np.asarray(drafts[r]), pars[r], c.next_tok, p_rows,
+                                                  np.asarray(q_rows[r], dtype=np.float64), np.asarray(u_acc[r]), float(u_emit[r]))
+        c.pending = Pending(nk[r], nv[r], path, tok)
+        out.append((SampleResult(a, tok, m1, m2, logits[r]), path))
+    return out

@@ -561,3 +561,30 @@ def test_stochastic_chain_two_steps_follow_the_joint_distribution():
         joint[t1, t2] += 1
     want = p1[:, None] * p2
     assert np.max(np.abs(joint / N - want)) < 5 * np.sqrt(0.25 / N)
+
+
+def test_stochastic_tree_rule_preserves_the_server_distribution():
+    """A root with three sibling proposals drawn independently from q: the first new token of the stream
+    (the accepted sibling's token, or the emitted one) must follow p; and a chain-shaped tree must behave
+    exactly like the chain rule."""
+    rng = np.random.default_rng(13)
+    V, N = 5, 80000
+    p = rng.dirichlet(np.ones(V)); q = rng.dirichlet(np.ones(V))
+    par = np.array([-1, 0, 0, 0])
+    cnt = np.zeros(V)
+    P = np.stack([p, p, p, p]); Q = np.stack([q, q, q, q])
+    for _ in range(N):
+        xs = rng.choice(V, size=3, p=q)
+        a, tok, path, _, _ = vo.accept_sample_tree(np.array([0, *xs]), par, 0, P, Q, rng.random(4), rng.random())
+        cnt[xs[path[1] - 1] if a == 2 else tok] += 1
+    sigma = np.sqrt(p * (1 - p) / N)
+    assert np.all(np.abs(cnt / N - p) < 5 * sigma + 1e-4), (cnt / N, p)
+    # chain-shaped tree == chain rule, decision by decision
+    for _ in range(200):
+        n = 5
+        d = np.concatenate([[0], rng.integers(0, V, n - 1)])
+        Pr = rng.dirichlet(np.ones(V), size=n); Qr = rng.dirichlet(np.ones(V), size=n)
+        u, ue = rng.random(n), rng.random()
+        a1, t1, _, _ = vo.accept_sample_chain(d, 0, Pr, Qr, u, ue)
+        a2, t2, path, _, _ = vo.accept_sample_tree(d, np.arange(-1, n - 1), 0, Pr, Qr, u, ue)
+        assert (a1, t1) == (a2, t2) and path == list(range(a1))
