@@ -190,31 +190,35 @@ typedef struct {
 int sev_verify_ex(const sev_model *weights, sev_kv *kv_cache, const sev_verify_args *args,
                   void *stream);
 
-/* Stochastic verification of chains: the rule the paper's method inherits from speculative
- * sampling (section 4.1: the cycle preserves the server model's output distribution exactly;
- * section 5: all models run at temperature 0.7).  One forward over the draft block as in
- * sev_verify; then, per request: candidate 0 must be the token the server emitted in the
- * previous step (the slot's next token; no random number is spent on it); candidate i >= 1,
- * drawn by the edge from its distribution q_i, is accepted iff u_accept[b][i] * q_i(x_i) <
- * p_{i-1}(x_i), p_{i-1} = softmax(logits after candidate i-1 / temperature); at the first
- * rejection the emitted token is drawn from the normalised residual max(0, p_{i-1} - q_i), after
- * full acceptance from p of the last candidate, in both cases by inverse CDF in token-id order
- * with u_emit[b].  All random numbers are inputs.  The slot is left pending exactly as after
- * sev_verify (accepted prefix, emitted token as the next token): sev_kv_commit / sev_kv_rollback
- * apply.  Trees are not supported by this entry point.
+/* Stochastic verification: the rule the paper's method inherits from speculative sampling
+ * (section 4.1: the cycle preserves the server model's output distribution exactly; section 5:
+ * all models run at temperature 0.7), in its multi-step form for trees (section 2, tree-based
+ * speculative decoding).  One forward over the draft block as in sev_verify_ex; then, per
+ * request: the block's root must be the token the server emitted in the previous step (a node
+ * with parent -1 whose token is the slot's next token, lowest index first; no random number is
+ * spent on it; without one nothing is accepted and that token is returned).  At the current
+ * node, p = softmax(logits computed there / temperature); its children are tried in index
+ * order: child c (token x, drawn by the edge from q_c) is accepted iff u_accept[b][c] * q_c(x) <
+ * p(x); a rejection replaces p by the normalised residual max(0, p - q_c); an acceptance moves
+ * to c.  When no child is left, the emitted token is drawn from the current p by inverse CDF in
+ * token-id order with u_emit[b].  A chain is the tree whose node i has parent i - 1 (parents =
+ * NULL).  All random numbers are inputs.  The slot is left pending exactly as after sev_verify_ex
+ * (accepted path, emitted token as the next token): sev_kv_commit / sev_kv_rollback apply.
+ * More than 16 rejected siblings at one node set error flag bit 3 (the rest are ignored).
  *   draft_probs   [device] float32[sum of draft lengths][vocab], rows packed like the GEMM rows
  *                 (request 0's candidates, then request 1's, ...); row of candidate 0 is unused
  *   u_accept      [device] float32[B][k_max], u_emit [device] float32[B], all in [0, 1)
  *   logits_ws     [device] float32[sum of draft lengths][vocab]: caller-provided workspace; holds
  *                 the block's logits on return
  *   accept_len, emitted_token [device] int32[B]
- * Errors as sev_verify_ex. */
+ * Errors as sev_verify_ex (trees: k_max <= 64 nodes, parents precede children). */
 typedef struct {
     int32_t B, k_max;
     const int32_t *slots;         /* [host] or NULL */
     const int32_t *prefix_lens;   /* [host] */
     const int32_t *draft_lens;    /* [host] or NULL */
     const int32_t *draft_tokens;  /* [device] int32[B][k_max] */
+    const int32_t *parents;       /* [device] int32[B][k_max] or NULL (chains), as in sev_verify_args */
     const float *draft_probs;
     const float *u_accept;
     const float *u_emit;
@@ -222,6 +226,7 @@ typedef struct {
     float *logits_ws;
     int32_t *accept_len;
     int32_t *emitted_token;
+    int32_t *accept_path;         /* [device] int32[B][k_max] accepted node indices, -1 padded; may be NULL */
 } sev_sample_args;
 
 int sev_verify_sample(const sev_model *weights, sev_kv *kv_cache, const sev_sample_args *args, void *stream);

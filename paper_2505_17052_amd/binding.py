@@ -30,9 +30,9 @@ class VerifyArgs(C.Structure):
 
 class SampleArgs(C.Structure):
     _fields_ = [("B", C.c_int32), ("k_max", C.c_int32), ("slots", C.c_void_p), ("prefix_lens", C.c_void_p),
-                ("draft_lens", C.c_void_p), ("draft_tokens", C.c_void_p), ("draft_probs", C.c_void_p),
+                ("draft_lens", C.c_void_p), ("draft_tokens", C.c_void_p), ("parents", C.c_void_p), ("draft_probs", C.c_void_p),
                 ("u_accept", C.c_void_p), ("u_emit", C.c_void_p), ("temperature", C.c_float),
-                ("logits_ws", C.c_void_p), ("accept_len", C.c_void_p), ("emitted_token", C.c_void_p)]
+                ("logits_ws", C.c_void_p), ("accept_len", C.c_void_p), ("emitted_token", C.c_void_p), ("accept_path", C.c_void_p)]
 
 
 def lib_path() -> str:
@@ -251,19 +251,22 @@ def verify_ex(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor
 
 
 def verify_sample(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor, k_max: int, draft_probs: torch.Tensor,
-                  u_accept: torch.Tensor, u_emit: torch.Tensor, temperature: float, slots=None, draft_lens=None):
-    """sev_verify_sample: returns a dict of device tensors (accept_len, emitted_token, logits)."""
+                  u_accept: torch.Tensor, u_emit: torch.Tensor, temperature: float, slots=None, draft_lens=None,
+                  parents: torch.Tensor = None):
+    """sev_verify_sample: returns a dict of device tensors (accept_len, emitted_token, accept_path, logits)."""
     pl, sl, dl = _host_i32(prefix_lens), _host_i32(slots), _host_i32(draft_lens)
     B = len(pl)
     rows = int(dl.sum()) if dl is not None else B * k_max
     dev = model.device
     out = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
            "emitted_token": torch.empty(B, dtype=torch.int32, device=dev),
+           "accept_path": torch.empty(B, k_max, dtype=torch.int32, device=dev),
            "logits": torch.empty(rows, model.desc.vocab, dtype=torch.float32, device=dev)}
     assert draft_probs.dtype == torch.float32 and tuple(draft_probs.shape) == (rows, model.desc.vocab) and draft_probs.is_contiguous()
     assert u_accept.dtype == torch.float32 and tuple(u_accept.shape) == (B, k_max) and u_emit.dtype == torch.float32
-    a = SampleArgs(B, k_max, _hp(sl), _hp(pl), _hp(dl), _dp(draft_tokens), _dp(draft_probs), _dp(u_accept), _dp(u_emit),
-                   float(temperature), _dp(out["logits"]), _dp(out["accept_len"]), _dp(out["emitted_token"]))
+    a = SampleArgs(B, k_max, _hp(sl), _hp(pl), _hp(dl), _dp(draft_tokens), _dp(parents), _dp(draft_probs), _dp(u_accept), _dp(u_emit),
+                   float(temperature), _dp(out["logits"]), _dp(out["accept_len"]), _dp(out["emitted_token"]),
+                   _dp(out["accept_path"]))
     _check(lib().sev_verify_sample(model.handle, kv.handle, C.byref(a), _stream_ptr()), "sev_verify_sample")
     return out
 

@@ -298,19 +298,24 @@ __global__ void commit_state_kernel(SlotList sl, int B, int rollback, int32_t *s
 }
 
 // ---------------------------------------------------------------------------
-// stochastic verification of chains (paper section 4.1: the draft/verify cycle preserves the
-// server model's output distribution, by the accept / resample rule of speculative sampling;
-// section 5: temperature 0.7).  All random numbers are inputs.
+// stochastic verification (paper section 4.1: the draft/verify cycle preserves the server
+// model's output distribution, by the accept / resample rule of speculative sampling, in its
+// multi-step form for trees; section 5: temperature 0.7).  All random numbers are inputs.
 //
 // softmax_stats_kernel: one block per row: the row's largest logit and the sum of
 //   exp((logit - max) / T).
-// sample_accept_kernel: one block per request.  Thread 0 walks the chain: candidate 0 must be the
-//   server's own previous token; candidate i >= 1 is accepted iff u_acc[i] * q_i(x_i) < p_{i-1}(x_i).
-//   Then the whole block draws the emitted token by inverse CDF in token-id order from the
-//   residual max(0, p - q) at the first rejection (p itself after full acceptance, or when the
-//   residual is empty): every thread sums a contiguous range of ids, the ranges are scanned in
-//   order, and the thread whose range holds u * total walks it.  Same order every run.
+// sample_walk_kernel: one block per request.  The block's root must be the server's own previous
+//   token.  At the current node, with p = the server distribution computed there, the children
+//   are tried in index order: child c (token x, edge distribution q_c) is accepted iff
+//   u_acc[c] * q_c(x) < p(x); a rejection replaces p by the normalised residual max(0, p - q_c)
+//   (the normaliser is a block-wide sum over the vocabulary, in a fixed order); an acceptance
+//   moves to c.  When no child is left the emitted token is drawn from the current p by inverse
+//   CDF in token-id order: every thread sums a contiguous range of ids, the ranges are scanned
+//   in order, and the range that holds u_emit * total is walked.  Chains are trees whose node
+//   i has parent i - 1.
 // ---------------------------------------------------------------------------
+#define SEV_MAX_REJ 16   // rejected siblings remembered at one node
+
 __global__ __launch_bounds__(1024) void softmax_stats_kernel(const float *logits, int vocab, float inv_t, float2 *stats) {
     __shared__ float red[16];
     const float *row = logits + (size_t)blockIdx.x * vocab;
@@ -336,104 +341,143 @@ __global__ __launch_bounds__(1024) void softmax_stats_kernel(const float *logits
     }
 }
 
-__global__ __launch_bounds__(1024) void sample_accept_kernel(DevPlan p, int k_max, const int32_t *tokens, const float *logits,
-                                                             const float *draft_probs, const float2 *stats, int vocab, float inv_t,
-                                                             const float *u_acc, const float *u_emit, const int32_t *next_tok,
-                                                             int32_t *pend_n, int32_t *pend_a, int32_t *pend_bonus, int32_t *pend_path,
-                                                             int32_t *accept_len, int32_t *emitted) {
-    __shared__ int s_a, s_rej;
-    __shared__ float s_part[1024], s_partp[1024];
-    __shared__ float s_total, s_totalp;
+struct WalkState {
+    int cur, a, nrej, child, action;       // action: 0 accepted a child, 1 rejected one (in rej[nrej]), 2 no child left
+    int rej[SEV_MAX_REJ + 1];
+    float R[SEV_MAX_REJ + 1];
+    int path[SEV_MAX_DRAFT];
+};
+
+__global__ __launch_bounds__(1024) void sample_walk_kernel(DevPlan p, int k_max, const int32_t *tokens, const int32_t *parents,
+                                                           const float *logits, const float *draft_probs, const float2 *stats, int vocab,
+                                                           float inv_t, const float *u_acc, const float *u_emit, const int32_t *next_tok,
+                                                           uint32_t *err, int32_t *pend_n, int32_t *pend_a, int32_t *pend_bonus,
+                                                           int32_t *pend_path, int32_t *accept_len, int32_t *emitted, int32_t *path_out) {
+    __shared__ WalkState s;
+    __shared__ float s_part[1024];
+    __shared__ float s_total;
+    __shared__ int s_pick;
     const int b = blockIdx.x, t = threadIdx.x;
     const int slot = p.req_slot[b], n = p.req_n[b], row0 = p.req_row0[b];
+    const int32_t *tk = tokens + (size_t)b * k_max;
+    const int32_t *par = parents ? parents + (size_t)b * k_max : nullptr;
+    auto parent_of = [&](int c) {
+        const int q = par ? par[c] : c - 1;
+        return (q < -1 || q >= c) ? -1 : q;
+    };
+    // value at token v of the current distribution: the node's softmax, then one residual step per rejected sibling
+    auto current = [&](int v) {
+        const float2 st = stats[row0 + s.cur];
+        float r = expf((logits[(size_t)(row0 + s.cur) * vocab + v] - st.x) * inv_t) / st.y;
+        for (int j = 0; j < s.nrej; ++j) r = fmaxf(r - draft_probs[(size_t)(row0 + s.rej[j]) * vocab + v], 0.f) / s.R[j];
+        return r;
+    };
     if (t == 0) {
-        int a = 0, rej = 0;
-        if (tokens[b * k_max] == next_tok[slot]) {
-            a = 1;
-            for (int i = 1; i < n; ++i) {
-                const int x = tokens[b * k_max + i];
-                const float2 st = stats[row0 + i - 1];
-                const float pr = expf((logits[(size_t)(row0 + i - 1) * vocab + x] - st.x) * inv_t) / st.y;
-                const float q = draft_probs[(size_t)(row0 + i) * vocab + x];
-                if (u_acc[b * k_max + i] * q < pr) ++a;
-                else { rej = 1; break; }
-            }
-        }
-        s_a = a;
-        s_rej = rej;
+        s.cur = -1;
+        s.a = 0;
+        s.nrej = 0;
+        for (int c = 0; c < n; ++c)
+            if (parent_of(c) == -1 && tk[c] == next_tok[slot]) { s.cur = c; break; }
+        if (s.cur >= 0) { s.path[0] = s.cur; s.a = 1; s.child = s.cur + 1; }
     }
     __syncthreads();
-    const int a = s_a, rej = s_rej;
     int tok = next_tok[slot];
-    if (a > 0) {
-        // weights over token ids: residual of (p after candidate a-1) against (q of candidate a), and p itself
-        const float *lrow = logits + (size_t)(row0 + a - 1) * vocab;
-        const float *qrow = draft_probs + (size_t)(row0 + (rej ? a : a - 1)) * vocab;     // unused without a rejection
-        const float2 st = stats[row0 + a - 1];
-        const float inv_z = 1.0f / st.y;
+    if (s.cur >= 0) {
         const int per = (vocab + 1023) / 1024, v0 = t * per, v1 = min(vocab, v0 + per);
-        float sr = 0.f, sp = 0.f;
-        for (int v = v0; v < v1; ++v) {
-            const float pv = expf((lrow[v] - st.x) * inv_t) * inv_z;
-            sp += pv;
-            if (rej) sr += fmaxf(pv - qrow[v], 0.f);
-        }
-        s_part[t] = sr;
-        s_partp[t] = sp;
-        __syncthreads();
-        if (t == 0) {
-            float tr = 0.f, tp = 0.f;
-            for (int i = 0; i < 1024; ++i) { tr += s_part[i]; tp += s_partp[i]; }
-            s_total = tr;
-            s_totalp = tp;
-        }
-        __syncthreads();
-        const bool use_res = rej && s_total > 0.f;
-        const float total = use_res ? s_total : s_totalp;
-        const float target = u_emit[b] * total;
-        // thread 0 finds the range that holds the target (ranges in id order), then walks it
-        if (t == 0) {
-            const float *part = use_res ? s_part : s_partp;
-            float cum = 0.f;
-            int seg = 1023;
-            for (int i = 0; i < 1024; ++i) {
-                if (target < cum + part[i]) { seg = i; break; }
-                cum += part[i];
+        for (int guard = 0; guard <= 2 * SEV_MAX_DRAFT; ++guard) {          // every round consumes a child or ends the walk
+            if (t == 0) {
+                s.action = 2;
+                for (int c = s.child; c < n; ++c) {
+                    if (parent_of(c) != s.cur) continue;
+                    const int x = tk[c];
+                    const float px = current(x), qx = draft_probs[(size_t)(row0 + c) * vocab + x];
+                    s.child = c + 1;
+                    if (u_acc[(size_t)b * k_max + c] * qx < px) {
+                        s.cur = c;
+                        s.path[s.a++] = c;
+                        s.nrej = 0;
+                        s.action = 0;
+                    } else {
+                        s.rej[s.nrej] = c;
+                        s.action = 1;
+                    }
+                    break;
+                }
             }
-            const int w0 = seg * per, w1 = min(vocab, w0 + per);
-            int pick = -1, last_nonzero = -1;
-            for (int v = w0; v < w1; ++v) {
-                const float pv = expf((lrow[v] - st.x) * inv_t) * inv_z;
-                const float w = use_res ? fmaxf(pv - qrow[v], 0.f) : pv;
-                if (w > 0.f) last_nonzero = v;
-                if (target < cum + w) { pick = v; break; }
-                cum += w;
+            __syncthreads();
+            const int action = s.action;
+            if (action == 0) {
+                __syncthreads();                                              // everyone has read the action before thread 0 writes the next one
+                continue;
             }
-            if (pick < 0) pick = last_nonzero >= 0 ? last_nonzero : max(w0, 0);     // rounding at the very end of the range
-            s_a = pick;
+            // a block-wide pass over the vocabulary: the residual against the rejected child (action 1), or the
+            // current distribution itself for the draw (action 2); range sums in id order
+            const float *qrow = action == 1 ? draft_probs + (size_t)(row0 + s.rej[s.nrej]) * vocab : nullptr;
+            float sum = 0.f;
+            for (int v = v0; v < v1; ++v) {
+                const float r = current(v);
+                sum += qrow ? fmaxf(r - qrow[v], 0.f) : r;
+            }
+            s_part[t] = sum;
+            __syncthreads();
+            if (t == 0) {
+                float tot = 0.f;
+                for (int i = 0; i < 1024; ++i) tot += s_part[i];
+                s_total = tot;
+                if (action == 1) {
+                    if (s.nrej >= SEV_MAX_REJ) atomicOr(err, 8u);           // more rejected siblings than the walk remembers
+                    else if (tot > 0.f) { s.R[s.nrej] = tot; ++s.nrej; }    // an empty residual leaves the distribution as it is
+                }
+            }
+            __syncthreads();
+            if (action == 1) continue;
+            if (t == 0) {
+                const float target = u_emit[b] * s_total;
+                float cum = 0.f;
+                int seg = 1023;
+                for (int i = 0; i < 1024; ++i) {
+                    if (target < cum + s_part[i]) { seg = i; break; }
+                    cum += s_part[i];
+                }
+                const int w0 = seg * per, w1 = min(vocab, w0 + per);
+                int pick = -1, last_nonzero = -1;
+                for (int v = w0; v < w1; ++v) {
+                    const float w = current(v);
+                    if (w > 0.f) last_nonzero = v;
+                    if (target < cum + w) { pick = v; break; }
+                    cum += w;
+                }
+                if (pick < 0) pick = last_nonzero >= 0 ? last_nonzero : min(w0, vocab - 1);   // rounding at the very end of the range
+                s_pick = pick;
+            }
+            __syncthreads();
+            tok = s_pick;
+            break;
         }
-        __syncthreads();
-        tok = s_a;
     }
     if (t == 0) {
+        const int a = s.a;
         int32_t *path = pend_path + (size_t)slot * SEV_MAX_DRAFT;
-        for (int i = 0; i < SEV_MAX_DRAFT; ++i) path[i] = i < a ? i : -1;
+        for (int i = 0; i < SEV_MAX_DRAFT; ++i) path[i] = i < a ? s.path[i] : -1;
         pend_n[slot] = n;
         pend_a[slot] = a;
         pend_bonus[slot] = tok;
         accept_len[b] = a;
         emitted[b] = tok;
+        if (path_out)
+            for (int i = 0; i < k_max; ++i) path_out[(size_t)b * k_max + i] = i < a ? s.path[i] : -1;
     }
 }
 
-void launch_sample(const sev_kv *kv, int B, int k_max, int rows, const int32_t *tokens, const float *logits, const float *draft_probs,
-                   float2 *stats, float temperature, const float *u_acc, const float *u_emit, int32_t *accept_len, int32_t *emitted,
-                   hipStream_t st) {
+void launch_sample(const sev_kv *kv, int B, int k_max, int rows, const int32_t *tokens, const int32_t *parents, const float *logits,
+                   const float *draft_probs, float2 *stats, float temperature, const float *u_acc, const float *u_emit,
+                   int32_t *accept_len, int32_t *emitted, int32_t *accept_path, hipStream_t st) {
     const int vocab = kv->model->d.vocab;
     const float inv_t = 1.0f / temperature;
     hipLaunchKernelGGL(softmax_stats_kernel, dim3(rows), dim3(1024), 0, st, logits, vocab, inv_t, stats);
-    hipLaunchKernelGGL(sample_accept_kernel, dim3(B), dim3(1024), 0, st, kv->plan, k_max, tokens, logits, draft_probs, stats, vocab, inv_t,
-                       u_acc, u_emit, kv->next_tok, kv->pend_n, kv->pend_a, kv->pend_bonus, kv->pend_path, accept_len, emitted);
+    hipLaunchKernelGGL(sample_walk_kernel, dim3(B), dim3(1024), 0, st, kv->plan, k_max, tokens, parents, logits, draft_probs, stats, vocab,
+                       inv_t, u_acc, u_emit, kv->next_tok, kv->err_flags, kv->pend_n, kv->pend_a, kv->pend_bonus, kv->pend_path, accept_len,
+                       emitted, accept_path);
 }
 
 KvGeom sev_kv_geom(const sev_kv *kv);

@@ -603,8 +603,8 @@ static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStre
     {
         Prof p(kv, st, PROF_OTHER);
         if (c.draft_probs)
-            launch_sample(kv, c.B, c.tok_stride, (int)rows, c.tokens, c.logits, c.draft_probs, kv->row_stats, c.temperature, c.u_accept,
-                          c.u_emit, c.accept_len, c.bonus_token, st);
+            launch_sample(kv, c.B, c.tok_stride, (int)rows, c.tokens, c.parents, c.logits, c.draft_probs, kv->row_stats, c.temperature,
+                          c.u_accept, c.u_emit, c.accept_len, c.bonus_token, c.accept_path, st);
         else
             launch_accept(kv, c.B, c.tok_stride, c.mode, c.tokens, c.parents, c.accept_len, c.bonus_token, c.accept_path, st);
         if (c.row_argmax)
@@ -653,9 +653,9 @@ extern "C" int sev_verify_sample(const sev_model *m, sev_kv *kv, const sev_sampl
     BlockCall c;
     memset(&c, 0, sizeof(c));
     c.slots = a->slots; c.prefix_lens = a->prefix_lens; c.lens = a->draft_lens; c.n_all = a->k_max;
-    c.tokens = a->draft_tokens; c.tok_stride = a->k_max; c.tok_off = 0;
+    c.tokens = a->draft_tokens; c.tok_stride = a->k_max; c.tok_off = 0; c.parents = a->parents;
     c.B = a->B; c.mode = 0;
-    c.accept_len = a->accept_len; c.bonus_token = a->emitted_token; c.logits = a->logits_ws;
+    c.accept_len = a->accept_len; c.bonus_token = a->emitted_token; c.accept_path = a->accept_path; c.logits = a->logits_ws;
     c.draft_probs = a->draft_probs; c.u_accept = a->u_accept; c.u_emit = a->u_emit; c.temperature = a->temperature;
     return run_block(m, kv, c, (hipStream_t)stream);
 }

@@ -151,9 +151,9 @@ void launch_plan(const sev_kv *kv, const PlanArgs &pa, const int32_t *draft_toke
                  int chunk_pages, int n_items, hipStream_t st);
 void launch_accept(const sev_kv *kv, int B, int k_max, int mode, const int32_t *draft_tokens, const int32_t *parents,
                    int32_t *accept_len, int32_t *bonus, int32_t *accept_path, hipStream_t st);
-void launch_sample(const sev_kv *kv, int B, int k_max, int rows, const int32_t *tokens, const float *logits, const float *draft_probs,
-                   float2 *stats, float temperature, const float *u_acc, const float *u_emit, int32_t *accept_len, int32_t *emitted,
-                   hipStream_t st);
+void launch_sample(const sev_kv *kv, int B, int k_max, int rows, const int32_t *tokens, const int32_t *parents, const float *logits,
+                   const float *draft_probs, float2 *stats, float temperature, const float *u_acc, const float *u_emit,
+                   int32_t *accept_len, int32_t *emitted, int32_t *accept_path, hipStream_t st);
 void launch_commit(const sev_kv *kv, const int32_t *slots_dev_by_value, int B, bool rollback, hipStream_t st);
 void launch_kv_copy(const sev_kv *kv, int slot, int layer, int start, int n, void *k, void *v, int to_cache, hipStream_t st);
 void launch_argmax_rows_f32(const float *logits, int rows, int vocab, int32_t *out, hipStream_t st);
