@@ -476,7 +476,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     //   wreg[u] holds W(st);  xreg[u] holds X(st+2).
     // During the stage each fragment register is refilled from LDS with its stage st+1 contents right
     // after its last MFMA, so the LDS reads of the next stage overlap the MFMAs of this one, and
-    // X(st+2) goes from registers into the LDS buffer that stage st no longer reads.
+    // X(st+2) goes from registers into the LDS buffer that stage st no longer reads (free since the
+    // barrier that ended stage st-1).
     // The loop body is PF stages of straight-line code (no branches), which lets the compiler's
     // wait-count bookkeeping follow the loads across the back-edge.  The slice is padded to a multiple
     // of PF stages: padded stages re-load the last stage (cached) and feed zero activations.
@@ -534,41 +535,58 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         for (int u = 0; u < PF; ++u) {
             const int st = base + u;
             const u32x4 *xnext = xs + ((u + 1) & 1) * STAGE_U4 + lane;      // X(st+1)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                for (int b = 0; b < MT; ++b) {
-#pragma unroll
-                    for (int a = 0; a < NT; ++a) {
-                        const bf16x8 w = as_bf16x8(wreg[u][a][ks]);
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][0]), acc[a][b], 0, 0, 0);
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][1]), acc[a][b], 0, 0, 0);
-                    }
-                    xf[ks][b][0] = xnext[((ks * MT + b) * 2 + 0) * 64];
-                    xf[ks][b][1] = xnext[((ks * MT + b) * 2 + 1) * 64];
-                }
-            }
-            // interleave: after every NT*2 MFMAs (one fragment pair consumed) issue its two LDS refills
-#pragma unroll
-            for (int i = 0; i < KS * MT; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 2 * NT, 0);   // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // DS read
-            }
-            __builtin_amdgcn_sched_barrier(0);
             // X(st+2): registers -> the LDS buffer whose fragments (stage st) were read during stage st-1
             const bool live = st + 2 < n;
             u32x4 *xd = xs + (u & 1) * STAGE_U4 + threadIdx.x;
-#pragma unroll
-            for (int i = 0; i < XI; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
-            __builtin_amdgcn_sched_barrier(0);
-            // refill this slot: activations first, then weights (the order they will be waited on)
             const int sx = min(s_begin + st + PF + 2, s_last_stage), sw = min(s_begin + st + PF, s_last_stage);
+            // Everything else a stage has to do is spread between its MFMAs, so that the matrix pipe
+            // never waits for a run of address arithmetic, loads and LDS traffic at the stage's end:
+            // a weight fragment is refilled right after its last MFMA (column tiles are the outer loop),
+            // the LDS write of X(st+2) and the loads that refill its registers follow the first group,
+            // and every activation fragment is re-read from LDS (stage st+1) after its last use, which
+            // falls into the last column tile's group.
 #pragma unroll
-            for (int i = 0; i < XI; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+            for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
-            for (int a = 0; a < NT; ++a)
+                for (int a = 0; a < NT; ++a) {
+                    const bf16x8 w = as_bf16x8(wreg[u][a][ks]);
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
+                    for (int pl = 0; pl < 2; ++pl)
+#pragma unroll
+                        for (int b = 0; b < MT; ++b) {
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][pl]), acc[a][b], 0, 0, 0);
+                            if (a == NT - 1) xf[ks][b][pl] = xnext[((ks * MT + b) * 2 + pl) * 64];
+                        }
+                    wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
+                    if (ks == 0 && a == 0) {
+#pragma unroll
+                        for (int i = 0; i < XI; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
+#pragma unroll
+                        for (int i = 0; i < XI; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+                    }
+                }
+            }
+            // the same order for the instruction scheduler (0x008 MFMA, 0x100 DS read, 0x200 DS write, 0x020 VMEM read)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int a = 0; a < NT; ++a) {
+                    if (a < NT - 1) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 2 * MT, 0);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 2 * MT; ++i) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    if (ks == 0 && a == 0) {
+                        __builtin_amdgcn_sched_group_barrier(0x200, XI, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x020, XI, 0);
+                    }
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
         }
