@@ -494,20 +494,30 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         xsrc[i] = (const u32x4 *)g.X + ((size_t)ksl * g.m_tiles_total + mt0) * 128 + within;
     }
     const size_t x_stage = (size_t)KS * g.m_tiles_total * 128;      // 16-byte units per stage of all row tiles
-    const int s_last_stage = s_end - 1;
     const int n_pad = (n + PF - 1) / PF * PF;
+    // Every column group walks its K range from a different starting stage (and wraps around): the
+    // blocks that run at the same time would otherwise all read the same few KiB of activations at the
+    // same moment, i.e. hammer a few L2 channels while the others idle.  The row blocks of a column
+    // group share the rotation, so they still read their common weight tiles together.  Short split-K
+    // slices keep the common start: they are mostly pipeline fill, where sharing the first misses wins.
+    const int rot = n >= 64 ? (int)(((int64_t)cg * n) / g.col_groups) : 0;
+    auto phys = [&](int t) {                                        // logical stage -> stage index in K
+        int i = min(t, n - 1) + rot;
+        if (i >= n) i -= n;
+        return s_begin + i;
+    };
     const u32x4 zero4 = (u32x4){0u, 0u, 0u, 0u};
 
     {
         u32x4 x0[XI], x1[XI];
 #pragma unroll
         for (int i = 0; i < XI; ++i) {
-            x0[i] = xsrc[i][(size_t)s_begin * x_stage];
-            x1[i] = xsrc[i][(size_t)min(s_begin + 1, s_last_stage) * x_stage];
+            x0[i] = xsrc[i][(size_t)phys(0) * x_stage];
+            x1[i] = xsrc[i][(size_t)phys(1) * x_stage];
         }
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
-            const int sx = min(s_begin + u + 2, s_last_stage), sw = min(s_begin + u, s_last_stage);
+            const int sx = phys(u + 2), sw = phys(u);
 #pragma unroll
             for (int i = 0; i < XI; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
 #pragma unroll
@@ -538,7 +548,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             // X(st+2): registers -> the LDS buffer whose fragments (stage st) were read during stage st-1
             const bool live = st + 2 < n;
             u32x4 *xd = xs + (u & 1) * STAGE_U4 + threadIdx.x;
-            const int sx = min(s_begin + st + PF + 2, s_last_stage), sw = min(s_begin + st + PF, s_last_stage);
+            const int sx = phys(st + PF + 2), sw = phys(st + PF);
             // Everything else a stage has to do is spread between its MFMAs, so that the matrix pipe
             // never waits for a run of address arithmetic, loads and LDS traffic at the stage's end:
             // a weight fragment is refilled right after its last MFMA (column tiles are the outer loop),
