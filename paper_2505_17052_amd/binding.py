@@ -35,6 +35,10 @@ class SampleArgs(C.Structure):
                 ("logits_ws", C.c_void_p), ("accept_len", C.c_void_p), ("emitted_token", C.c_void_p), ("accept_path", C.c_void_p)]
 
 
+class SchedDesc(C.Structure):
+    _fields_ = [("max_batch", C.c_int32), ("max_rows", C.c_int32), ("min_batch", C.c_int32), ("max_wait_us", C.c_int64)]
+
+
 def lib_path() -> str:
     return os.path.join(_HERE, "libsev.so")
 
@@ -75,6 +79,14 @@ def lib():
         "sev_profile_enable": (i32, [vp, C.c_uint]),
         "sev_profile_read": (i32, [vp, i32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "sev_profile_name": (C.c_char_p, [i32]),
+        "sev_sched_create": (i32, [C.POINTER(SchedDesc), C.POINTER(vp)]),
+        "sev_sched_destroy": (i32, [vp]),
+        "sev_sched_submit": (i32, [vp, i32, i32, i64]),
+        "sev_sched_next_batch": (i32, [vp, i64, vp, vp, C.POINTER(C.c_int32), C.POINTER(C.c_int64)]),
+        "sev_sched_pending": (i32, [vp]),
+        "sev_sched_record_verify": (i32, [vp, i64]),
+        "sev_sched_verify_estimate": (i64, [vp]),
+        "sev_sched_calibrate_depth": (i32, [i64, i64, i64, i32, i32]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -287,3 +299,50 @@ def kv_commit(kv: KVCache, slots, B: int):
 def kv_rollback(kv: KVCache, slots, B: int):
     sl = _host_i32(slots)
     _check(lib().sev_kv_rollback(kv.handle, _hp(sl), B, _stream_ptr()), "sev_kv_rollback")
+
+
+class Scheduler:
+    """Handle of the server-side batch former (sev_sched_*): host code, needs no GPU."""
+
+    def __init__(self, max_batch: int, max_rows: int, min_batch: int = 1, max_wait_us: int = 0):
+        self.desc = SchedDesc(max_batch, max_rows, min_batch, max_wait_us)
+        self.h = C.c_void_p()
+        _check(lib().sev_sched_create(C.byref(self.desc), C.byref(self.h)), "sev_sched_create")
+        self._req = np.zeros(max(max_batch, 1), dtype=np.int32)
+        self._rows = np.zeros(max(max_batch, 1), dtype=np.int32)
+
+    def submit(self, request: int, n_draft: int, arrival_us: int):
+        _check(lib().sev_sched_submit(self.h, request, n_draft, arrival_us), "sev_sched_submit")
+
+    def next_batch(self, now_us: int):
+        """Returns ([(request, n_draft)], wake_us)."""
+        n, wake = C.c_int32(0), C.c_int64(0)
+        _check(lib().sev_sched_next_batch(self.h, now_us, _hp(self._req), _hp(self._rows), C.byref(n), C.byref(wake)), "sev_sched_next_batch")
+        return [(int(self._req[i]), int(self._rows[i])) for i in range(n.value)], wake.value
+
+    def pending(self) -> int:
+        return lib().sev_sched_pending(self.h)
+
+    def record_verify(self, duration_us: int):
+        _check(lib().sev_sched_record_verify(self.h, duration_us), "sev_sched_record_verify")
+
+    def verify_estimate(self) -> int:
+        return lib().sev_sched_verify_estimate(self.h)
+
+    def close(self):
+        if self.h:
+            lib().sev_sched_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def calibrate_depth(t_verify_us: int, t_draft_fwd_us: int, rtt_us: int, min_depth: int = 1, max_depth: int = 64) -> int:
+    d = lib().sev_sched_calibrate_depth(t_verify_us, t_draft_fwd_us, rtt_us, min_depth, max_depth)
+    if d < 0:
+        _check(d, "sev_sched_calibrate_depth")
+    return d

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsev.so")
-SOURCES = ["sev_api.hip", "kernels_common.hip", "kernels_f32.hip", "kernels_bf16.hip"]
+SOURCES = ["sev_api.hip", "kernels_common.hip", "kernels_f32.hip", "kernels_bf16.hip", "sev_sched.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result"]
 
@@ -18,7 +18,7 @@ def build(verbose: bool = False) -> str:
     bdir = os.path.join(HERE, "_build")
     os.makedirs(bdir, exist_ok=True)
     for s in SOURCES:
-        o = os.path.join(bdir, s.replace(".hip", ".o"))
+        o = os.path.join(bdir, os.path.splitext(s)[0] + ".o")
         objs.append(o)
         cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o]
         if verbose:
