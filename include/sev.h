@@ -104,7 +104,10 @@ size_t sev_kv_pool_bytes(const sev_model *m, int64_t n_pages, int page_size);
  * allocated [device] pool (256-byte aligned, >= sev_kv_pool_bytes).  Also allocates the
  * activation workspace for up to max_rows draft tokens per call (sum over the
  * batch) — the only device allocation the library makes.  page_size must be 16.
- * Every slot starts empty (length 0, no pages, next token -1). */
+ * Every slot starts empty (length 0, no pages, next token -1).
+ * The pool must be cleared (all zero bytes) before its first use: cache slots that a mask hides
+ * (the tail of a request's last page, padding) still enter the attention products with weight 0,
+ * so they must not hold NaN or infinity bit patterns. */
 int sev_kv_create(const sev_model *m, int max_requests, int max_rows, int64_t n_pages,
                   int page_size, void *pool /*[device]*/, size_t pool_bytes, sev_kv **out);
 int sev_kv_destroy(sev_kv *kv);
@@ -180,6 +183,13 @@ typedef struct {
     const int32_t *parents;       /* [device] int32[B][k_max] or NULL for chains                        */
     int32_t mode;                 /* 0 = verify; 1 = append: accept every candidate of a chain          */
                                   /*     (cache fill / teacher forcing), bonus = arg-max after the last */
+                                  /* | 2 = padded-KV comparison variant (bfloat16 path): the paper's     */
+                                  /*     handling of heterogeneous batches (section 4.3: every sequence  */
+                                  /*     padded to the longest of the batch under a per-sequence mask):  */
+                                  /*     attention walks max_b(prefix_len + draft_len) cache slots of    */
+                                  /*     EVERY request, the ones past its own end masked.  Same results, */
+                                  /*     the longest sequence's cost; every slot's pages must cover that */
+                                  /*     length (SEV_ENOSPACE otherwise)                                 */
     int32_t *accept_len;          /* [device] int32[B]                                                  */
     int32_t *bonus_token;         /* [device] int32[B]                                                  */
     int32_t *accept_path;         /* [device] int32[B][k_max] accepted candidate indices in order, -1 padded; may be NULL */

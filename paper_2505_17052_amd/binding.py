@@ -241,14 +241,14 @@ def verify(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor, d
 
 def verify_ex(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor, k_max: int, slots=None,
               draft_lens=None, parents: torch.Tensor = None, mode: int = 0, want_path=False, want_argmax=False,
-              want_logits=False):
+              want_logits=False, accept_len: torch.Tensor = None, bonus_token: torch.Tensor = None):
     """sev_verify_ex: returns a dict of device tensors (accept_len, bonus_token and the requested extras)."""
     pl, sl, dl = _host_i32(prefix_lens), _host_i32(slots), _host_i32(draft_lens)
     B = len(pl)
     rows = int(dl.sum()) if dl is not None else B * k_max
     dev = model.device
-    out = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
-           "bonus_token": torch.empty(B, dtype=torch.int32, device=dev)}
+    out = {"accept_len": accept_len if accept_len is not None else torch.empty(B, dtype=torch.int32, device=dev),
+           "bonus_token": bonus_token if bonus_token is not None else torch.empty(B, dtype=torch.int32, device=dev)}
     if want_path:
         out["accept_path"] = torch.empty(B, k_max, dtype=torch.int32, device=dev)
     if want_argmax:

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
         d.pend_n[slot] = 0;                      // a new verify drops whatever was pending
         d.pend_P[slot] = P;
         my_groups = (d.G * n + 31) / 32;
-        const int pages = (P + n + SEV_PAGE - 1) / SEV_PAGE;
+        const int pages = (max(P + n, a.pad_tokens) + SEV_PAGE - 1) / SEV_PAGE;
         my_chunks = (pages + d.chunk_pages - 1) / d.chunk_pages;
         my_items = my_groups * my_chunks;
         s_row0[t + 1] = n;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
             depth_prev = depth;
         }
         // attention work items of this request: its pages are split evenly over my_chunks chunks
-        const int pages = (P + n + SEV_PAGE - 1) / SEV_PAGE;
+        const int pages = (max(P + n, a.pad_tokens) + SEV_PAGE - 1) / SEV_PAGE;
         const int cpp = (pages + my_chunks - 1) / my_chunks;
         int it = s_item0[t], g0 = s_grp0[t];
         for (int rg = 0; rg < my_groups; ++rg) {

@@ -507,7 +507,7 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     auto items_for = [&](int64_t cp) {
         int64_t items = 0;
         for (int b = 0; b < pa.B; ++b) {
-            const int64_t pages = (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE;
+            const int64_t pages = (std::max(pa.prefix[b] + pa.nd[b], pa.pad_tokens) + SEV_PAGE - 1) / SEV_PAGE;
             items += ((G * pa.nd[b] + 31) / 32) * ((pages + cp - 1) / cp);
         }
         return items;
@@ -519,7 +519,8 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     // compute unit needs about 0.75 us per page pair and SIMD).
     *direct = false;
     int64_t max_pages = 0;
-    for (int b = 0; b < pa.B; ++b) max_pages = std::max<int64_t>(max_pages, (pa.prefix[b] + pa.nd[b] + SEV_PAGE - 1) / SEV_PAGE);
+    for (int b = 0; b < pa.B; ++b)
+        max_pages = std::max<int64_t>(max_pages, (std::max(pa.prefix[b] + pa.nd[b], pa.pad_tokens) + SEV_PAGE - 1) / SEV_PAGE);
     if (!getenv("SEV_TUNE_CP") && max_pages <= 64 && total_groups * d.n_kv_heads * 2 >= n_cu &&
         total_groups <= kv->max_items) {
         *direct = true;
@@ -566,7 +567,8 @@ static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStre
     PlanArgs pa;
     pa.B = c.B;
     pa.k_max = c.tok_stride;
-    pa.mode = c.mode;
+    pa.mode = c.mode & 1;
+    pa.pad_tokens = 0;
     pa.tok_stride = c.tok_stride;
     pa.tok_off = c.tok_off;
     int64_t rows = 0;
@@ -587,6 +589,16 @@ static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStre
         rows += n;
     }
     if (rows > kv->max_rows) return sev_fail(SEV_ENOSPACE, "%lld tokens exceed max_rows=%d", (long long)rows, kv->max_rows);
+    if (c.mode & 2) {
+        // the paper's formulation of a heterogeneous batch: every sequence padded to the longest one,
+        // a dense mask hiding the padding; here: every request's attention walks that many cache slots
+        if (m->d.dtype != SEV_BF16) return sev_fail(SEV_EINVAL, "the padded-KV variant exists for the bfloat16 path only");
+        for (int b = 0; b < c.B; ++b) pa.pad_tokens = std::max(pa.pad_tokens, pa.prefix[b] + pa.nd[b]);
+        for (int b = 0; b < c.B; ++b)
+            if ((int64_t)pa.pad_tokens > (int64_t)kv->host_pages[pa.slot[b]] * SEV_PAGE)
+                return sev_fail(SEV_ENOSPACE, "request %d: padding to %d tokens exceeds the %d pages of slot %d", b, pa.pad_tokens,
+                                kv->host_pages[pa.slot[b]], pa.slot[b]);
+    }
     int n_items = 0, n_groups = 0, cp = 64;
     bool att_direct = false;
     if (m->d.dtype == SEV_BF16) {
@@ -606,7 +618,7 @@ static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStre
             launch_sample(kv, c.B, c.tok_stride, (int)rows, c.tokens, c.parents, c.logits, c.draft_probs, kv->row_stats, c.temperature,
                           c.u_accept, c.u_emit, c.accept_len, c.bonus_token, c.accept_path, st);
         else
-            launch_accept(kv, c.B, c.tok_stride, c.mode, c.tokens, c.parents, c.accept_len, c.bonus_token, c.accept_path, st);
+            launch_accept(kv, c.B, c.tok_stride, c.mode & 1, c.tokens, c.parents, c.accept_len, c.bonus_token, c.accept_path, st);
         if (c.row_argmax)
             SEV_HIP(hipMemcpyAsync(c.row_argmax, kv->row_argmax, (size_t)rows * 4, hipMemcpyDeviceToDevice, st));
     }
@@ -621,8 +633,8 @@ extern "C" int sev_verify_ex(const sev_model *m, sev_kv *kv, const sev_verify_ar
     if (a->k_max < 1 || a->k_max > SEV_MAX_DRAFT) return sev_fail(SEV_EINVAL, "k=%d outside 1..%d", a->k_max, SEV_MAX_DRAFT);
     if (!a->prefix_lens || !a->draft_tokens || !a->accept_len || !a->bonus_token)
         return sev_fail(SEV_EINVAL, "prefix_lens, draft_tokens, accept_len and bonus_token are required");
-    if (a->mode != 0 && a->mode != 1) return sev_fail(SEV_EINVAL, "mode must be 0 (verify) or 1 (append)");
-    if (a->mode == 1 && a->parents) return sev_fail(SEV_EINVAL, "append mode takes chains only");
+    if (a->mode < 0 || a->mode > 3) return sev_fail(SEV_EINVAL, "mode must be 0 (verify) or 1 (append), optionally | 2 (padded KV)");
+    if ((a->mode & 1) && a->parents) return sev_fail(SEV_EINVAL, "append mode takes chains only");
     if (a->draft_lens)
         for (int b = 0; b < a->B; ++b)
             if (a->draft_lens[b] < 1 || a->draft_lens[b] > a->k_max)

@@ -53,6 +53,7 @@ struct sev_model {
 // Per-call description handed to the plan kernel by value.
 struct PlanArgs {
     int B, k_max, mode;
+    int pad_tokens;           // > 0: attention walks every request's pages up to this many tokens (padded-KV comparison variant)
     int tok_stride, tok_off;  // token of node i of request b: tokens[b * tok_stride + tok_off + i]
     int32_t slot[SEV_MAX_BATCH];
     int32_t prefix[SEV_MAX_BATCH];
