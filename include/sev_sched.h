@@ -8,7 +8,8 @@
  *         server verification time  ~=  edge drafting time + network round trip,
  * a new batch is complete exactly when the previous verification ends and the server never idles.
  * This library holds the two decisions of that scheme: which arrived blocks form the next batch,
- * and the draft depth that balances the equation from measured times.
+ * and the draft depth that balances the equation from measured times.  It also holds the edge's side
+ * of the protocol after a verification: the draft-alignment check.
  *
  * All times are int64 microseconds on a clock the caller owns (wall clock or a simulated one); the
  * scheduler never reads a clock itself, so a replay is deterministic.
@@ -71,6 +72,22 @@ int64_t sev_sched_verify_estimate(const sev_sched *s);
  * t_draft_fwd_us < 1, min_depth < 1 or max_depth < min_depth.  (The paper's example: verification
  * 94.2 ms, 11 ms per draft pass: depth 7 at 15 ms RTT, 5 at 40 ms, 4 at 50 ms.) */
 int sev_sched_calibrate_depth(int64_t t_verify_us, int64_t t_draft_fwd_us, int64_t rtt_us, int32_t min_depth, int32_t max_depth);
+
+/* Edge-side post-verification update (paper: "Post-verification update", complete draft alignment).
+ * The edge holds a draft tree of n_nodes nodes in topological order (parents[i] in [-1, i), -1 = child
+ * of the committed prefix): the nodes it sent for verification and the ones it drafted proactively
+ * while the server was busy.  The server answers with the accepted path (node indices, root first) and
+ * one additional token.  If the last accepted node (the prefix, if nothing was accepted) has a child
+ * whose token equals that additional token, the draft is aligned: the edge keeps that child and
+ * everything below it and continues drafting from there; otherwise all drafted work is discarded.
+ *   kept[0 .. *n_kept)        indices of the kept nodes in increasing order; kept[0] is the matching
+ *                             child (lowest index if several match); *n_kept = 0: no alignment
+ *   new_parents[0 .. *n_kept) parent of each kept node as an index into kept[] (-1 for kept[0]): the
+ *                             tree to send next, rooted at the token the server just emitted
+ * kept and new_parents have room for n_nodes entries.  Errors: SEV_EINVAL for null pointers, parents
+ * out of range, an accept_path that is not a root-to-node path of the tree. */
+int sev_edge_align(const int32_t *parents, const int32_t *tokens, int32_t n_nodes, const int32_t *accept_path, int32_t accept_len,
+                   int32_t bonus_token, int32_t *kept, int32_t *new_parents, int32_t *n_kept);
 
 #ifdef __cplusplus
 }

@@ -122,3 +122,24 @@ def simulate(n_draft, draft_us, rtt_us, former, verify, n_batches):
             tokens[r] += m
             heapq.heappush(events, (now + down + draft_us[r] + up, 0, r))
     return {"log": log, "tokens": tokens, "busy_us": busy, "end_us": now}
+
+
+def edge_align(parents, tokens, accept_path, bonus_token):
+    """Complete draft alignment (paper, "Post-verification update"): the server accepted accept_path and
+    emitted bonus_token; if a child of the last accepted node (of the prefix, for an empty path) carries
+    that token, the edge keeps that child's subtree.  Written out naively: a node is kept iff walking up
+    its parents reaches the matching child.  Returns (kept indices ascending, parents re-indexed into kept)."""
+    last = accept_path[-1] if len(accept_path) else -1
+    heads = [i for i in range(len(parents)) if parents[i] == last and tokens[i] == bonus_token]
+    if not heads:
+        return [], []
+    head = min(heads)
+
+    def under_head(i):
+        while i != -1:
+            if i == head:
+                return True
+            i = parents[i]
+        return False
+    kept = [i for i in range(len(parents)) if under_head(i)]
+    return kept, [-1 if i == head else kept.index(parents[i]) for i in kept]

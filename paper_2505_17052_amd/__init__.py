@@ -6,7 +6,7 @@ streams.  There is no CPU or PyTorch fallback: if the library is missing or no G
 present, calls fail.
 """
 from .binding import (SevError, lib, lib_path, Model, KVCache, verify, verify_ex, verify_sample, prefill, kv_commit, kv_rollback,
-                      Scheduler, calibrate_depth, SEV_F32, SEV_BF16, W_KINDS)
+                      Scheduler, calibrate_depth, edge_align, SEV_F32, SEV_BF16, W_KINDS)
 
-__all__ = ["SevError", "lib", "lib_path", "Model", "KVCache", "verify", "verify_ex", "verify_sample", "prefill", "kv_commit", "kv_rollback", "Scheduler", "calibrate_depth",
+__all__ = ["SevError", "lib", "lib_path", "Model", "KVCache", "verify", "verify_ex", "verify_sample", "prefill", "kv_commit", "kv_rollback", "Scheduler", "calibrate_depth", "edge_align",
            "SEV_F32", "SEV_BF16", "W_KINDS"]

@@ -87,6 +87,7 @@ def lib():
         "sev_sched_record_verify": (i32, [vp, i64]),
         "sev_sched_verify_estimate": (i64, [vp]),
         "sev_sched_calibrate_depth": (i32, [i64, i64, i64, i32, i32]),
+        "sev_edge_align": (i32, [vp, vp, i32, vp, i32, i32, vp, vp, C.POINTER(C.c_int32)]),
     }
     for name, (res, args) in sig.items():
         f = getattr(L, name)
@@ -346,3 +347,13 @@ def calibrate_depth(t_verify_us: int, t_draft_fwd_us: int, rtt_us: int, min_dept
     if d < 0:
         _check(d, "sev_sched_calibrate_depth")
     return d
+
+
+def edge_align(parents, tokens, accept_path, bonus_token: int):
+    """sev_edge_align: returns (kept node indices, their parents as indices into kept); both empty without alignment."""
+    par, tok, path = _host_i32(parents), _host_i32(tokens), _host_i32(accept_path)
+    n = len(par)
+    kept, newp, nk = np.zeros(max(n, 1), dtype=np.int32), np.zeros(max(n, 1), dtype=np.int32), C.c_int32(0)
+    _check(lib().sev_edge_align(_hp(par), _hp(tok), n, _hp(path), len(path), int(bonus_token), _hp(kept), _hp(newp), C.byref(nk)),
+           "sev_edge_align")
+    return kept[:nk.value].tolist(), newp[:nk.value].tolist()

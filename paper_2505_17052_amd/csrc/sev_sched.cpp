@@ -120,3 +120,36 @@ extern "C" int sev_sched_calibrate_depth(int64_t t_verify_us, int64_t t_draft_fw
     const int64_t depth = (2 * budget + t_draft_fwd_us) / (2 * t_draft_fwd_us);   // nearest, halves up
     return (int)std::min<int64_t>(std::max<int64_t>(depth, min_depth), max_depth);
 }
+
+extern "C" int sev_edge_align(const int32_t *parents, const int32_t *tokens, int32_t n_nodes, const int32_t *accept_path, int32_t accept_len,
+                              int32_t bonus_token, int32_t *kept, int32_t *new_parents, int32_t *n_kept) {
+    if (!parents || !tokens || !kept || !new_parents || !n_kept || (accept_len > 0 && !accept_path))
+        return sev_fail(SEV_EINVAL, "null argument");
+    *n_kept = 0;
+    if (n_nodes < 0 || accept_len < 0 || accept_len > n_nodes) return sev_fail(SEV_EINVAL, "bad node or path count");
+    for (int i = 0; i < n_nodes; ++i)
+        if (parents[i] < -1 || parents[i] >= i) return sev_fail(SEV_EINVAL, "node %d: parent %d does not precede it", i, parents[i]);
+    int last = -1;
+    for (int j = 0; j < accept_len; ++j) {
+        const int c = accept_path[j];
+        if (c < 0 || c >= n_nodes || parents[c] != last) return sev_fail(SEV_EINVAL, "accept_path[%d] = %d does not continue the path", j, c);
+        last = c;
+    }
+    int head = -1;
+    for (int i = last + 1; i < n_nodes && head < 0; ++i)
+        if (parents[i] == last && tokens[i] == bonus_token) head = i;
+    if (head < 0) return SEV_OK;
+    // parents precede children: one sweep marks the subtree; new index = number of kept nodes before it
+    std::vector<int32_t> pos((size_t)n_nodes, -1);
+    int n = 0;
+    for (int i = head; i < n_nodes; ++i) {
+        const bool in = i == head || (parents[i] >= head && pos[parents[i]] >= 0);
+        if (!in) continue;
+        pos[i] = n;
+        kept[n] = i;
+        new_parents[n] = i == head ? -1 : pos[parents[i]];
+        ++n;
+    }
+    *n_kept = n;
+    return SEV_OK;
+}

@@ -191,3 +191,44 @@ def test_replay_driver_matches_oracle_simulation():
         got = replay(n_draft, draft_us, rtt, sev.Scheduler(max_batch, max_rows, min_batch, wait), make_verify(trial), 30)
         want = so.simulate(n_draft, draft_us, rtt, so.Former(max_batch, max_rows, min_batch, wait), make_verify(trial), 30)
         assert got == want, trial
+
+
+# ---------------------------------------------------------------- edge-side draft alignment
+
+def test_oracle_edge_align_hand_cases():
+    # sent: 0 -> 1 -> 2 (a chain); proactively drafted under the leaf 2: 3 (token 9) -> 4, and 5 (token 7) -> 6 -> 7
+    parents = [-1, 0, 1, 2, 3, 2, 5, 6]
+    tokens = [10, 11, 12, 9, 20, 7, 21, 22]
+    assert so.edge_align(parents, tokens, [0, 1, 2], 7) == ([5, 6, 7], [-1, 0, 1])      # aligned on the second head
+    assert so.edge_align(parents, tokens, [0, 1, 2], 9) == ([3, 4], [-1, 0])
+    assert so.edge_align(parents, tokens, [0, 1, 2], 8) == ([], [])                       # the extra token was not drafted
+    assert so.edge_align(parents, tokens, [0, 1], 7) == ([], [])                          # stopped early: 7 is not a child of node 1
+    assert so.edge_align(parents, tokens, [0, 1], 12) == ([2, 3, 4, 5, 6, 7], [-1, 0, 1, 0, 3, 4])
+    assert so.edge_align(parents, tokens, [], 10) == (list(range(8)), parents)            # nothing accepted, root matches the emitted token
+    assert so.edge_align(parents, tokens, [], 11) == ([], [])
+
+
+def test_library_edge_align_matches_oracle():
+    import paper_2505_17052_amd as sev
+    rng = np.random.default_rng(47)
+    aligned = 0
+    for trial in range(400):
+        n = int(rng.integers(1, 40))
+        parents = [-1] + [int(rng.integers(-1, i)) for i in range(1, n)]
+        tokens = [int(x) for x in rng.integers(0, 6, size=n)]                            # few token values: matches and duplicate siblings happen
+        path, cur = [], -1                                                                # a random root-to-node path
+        while rng.random() < 0.7:
+            kids = [i for i in range(n) if parents[i] == cur]
+            if not kids:
+                break
+            cur = int(rng.choice(kids))
+            path.append(cur)
+        bonus = int(rng.integers(0, 6))
+        got, want = sev.edge_align(parents, tokens, path, bonus), so.edge_align(parents, tokens, path, bonus)
+        assert got == want, (trial, parents, tokens, path, bonus)
+        aligned += bool(want[0])
+    assert 50 < aligned < 350
+    with pytest.raises(sev.SevError):
+        sev.edge_align([-1, 0, 1], [1, 2, 3], [0, 2], 5)                                 # 2 is not a child of 0
+    with pytest.raises(sev.SevError):
+        sev.edge_align([-1, 1], [1, 2], [], 5)                                           # a node cannot be its own parent
