@@ -449,8 +449,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const int tile0 = (cg * 4 + wave) * NT;
     const int mt0 = mb * MT;
     const int n_stages = g.k_steps / KS;
-    const int s_begin = (int)((int64_t)n_stages * split / g.splits);
-    const int s_end = (int)((int64_t)n_stages * (split + 1) / g.splits);
+    const int s_begin = (int)((unsigned)n_stages * (unsigned)split / (unsigned)g.splits);          // small numbers: 32-bit division
+    const int s_end = (int)((unsigned)n_stages * (unsigned)(split + 1) / (unsigned)g.splits);
     const int n = s_end - s_begin;
     const int mrow = lane & 31, nsub = 4 * (lane >> 5);
 
@@ -500,7 +500,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // same moment, i.e. hammer a few L2 channels while the others idle.  The row blocks of a column
     // group share the rotation, so they still read their common weight tiles together.  Short split-K
     // slices keep the common start: they are mostly pipeline fill, where sharing the first misses wins.
-    const int rot = n >= 64 ? (int)(((int64_t)cg * n) / g.col_groups) : 0;
+    const int rot = n >= 64 ? (int)((unsigned)cg * (unsigned)n / (unsigned)g.col_groups) : 0;
     auto phys = [&](int t) {                                        // logical stage -> stage index in K
         int i = min(t, n - 1) + rot;
         if (i >= n) i -= n;
@@ -540,7 +540,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
             for (int pl = 0; pl < 2; ++pl) xf[ks][b][pl] = xs[((ks * MT + b) * 2 + pl) * 64 + lane];
 
-    for (int base = 0; base < n_pad; base += PF) {
+    // One group of PF stages.  The last group of a slice issues no global loads: what it would
+    // prefetch lies beyond the slice, and the epilogue would have to wait for those loads to return
+    // before it may reuse their registers.
+    auto group = [&](int base, auto load_tag) {
+        constexpr bool LOAD = decltype(load_tag)::value;
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int st = base + u;
@@ -567,12 +571,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][pl]), acc[a][b], 0, 0, 0);
                             if (a == NT - 1) xf[ks][b][pl] = xnext[((ks * MT + b) * 2 + pl) * 64];
                         }
-                    wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
+                    if constexpr (LOAD) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
                     if (ks == 0 && a == 0) {
 #pragma unroll
                         for (int i = 0; i < XI; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
+                        if constexpr (LOAD) {
 #pragma unroll
-                        for (int i = 0; i < XI; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+                            for (int i = 0; i < XI; ++i) xreg[u][i] = xsrc[i][(size_t)sx * x_stage];
+                        }
                     }
                 }
             }
@@ -590,17 +596,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                         }
                     }
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                    if constexpr (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                     if (ks == 0 && a == 0) {
                         __builtin_amdgcn_sched_group_barrier(0x200, XI, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x020, XI, 0);
+                        if constexpr (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, XI, 0);
                     }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
             __syncthreads();
         }
-    }
+    };
+    for (int base = 0; base + PF < n_pad; base += PF) group(base, std::true_type{});
+    group(n_pad - PF, std::false_type{});
     SEV_TRACE_T(tr2);
 
     // ------------------------------------------------------------------ split-K: hand the slice to the fix-up kernel
