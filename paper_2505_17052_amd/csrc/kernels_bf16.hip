@@ -388,7 +388,12 @@ __device__ __forceinline__ void ssq_commit(const GemmArgs &g, float (*red)[128],
 // timing probes for tuning experiments (never compiled into the library proper)
 __device__ unsigned long long *g_trace;
 __device__ unsigned g_trace_pos, g_trace_cap;
-#define SEV_TRACE_T(var) const unsigned long long var = wall_clock64()
+__device__ __forceinline__ unsigned long long sev_trace_now() {     // pinned in program order (a plain clock read may be moved)
+    unsigned long long t;
+    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t) : : "memory");
+    return t;
+}
+#define SEV_TRACE_T(var) const unsigned long long var = sev_trace_now()
 extern "C" int sev_trace_begin(int cap) {
     unsigned long long *buf;
     if (hipMalloc(&buf, (size_t)cap * 64) != hipSuccess) return -1;
@@ -426,6 +431,12 @@ extern "C" int sev_trace_read(unsigned long long *host, int cap) {
 #define SEV_TRACE_END(t4)
 #endif
 
+// Kernel arguments live in memory and are fetched with scalar loads where the compiler first needs
+// them; an argument block of several cache lines can then cost one memory latency per line, one after
+// the other, in the middle of the kernel.  Naming one field of every line at the kernel's entry makes
+// all of those fetches start together.
+#define SEV_ARGS_NOW(...) asm volatile("" : : __VA_ARGS__)
+
 template <int MT, int NT, int EPI, int PF>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // a pipeline stage is KS k-steps of 16: two for the narrow tiles, one for NT = 4 (same 32 MFMAs per wave with MT = 4)
@@ -436,6 +447,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     __shared__ float red[4][128];
     SEV_TRACE_T(tr0);
     constexpr int STAGE_U4 = KS * MT * 2 * 64;          // uint4 per stage
+    if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.W), "s"(g.ssq_in), "s"(g.row_cs), "s"(g.q_planes));
+    else if constexpr (EPI == EPI_ARGMAX) SEV_ARGS_NOW("s"(g.W), "s"(g.ssq_in), "s"(g.lm_val), "s"(g.logits));
+    else SEV_ARGS_NOW("s"(g.W), "s"(g.ssq_in), "s"(g.act));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // Block index decode, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, each with its
     // own L2.  Blocks that share weight tiles (the row blocks of one column group) get ids 8 apart,
@@ -695,6 +709,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g) {
     __shared__ float red[4][128];
+    if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.row_cs), "s"(g.q_planes));
+    else SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.act));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int MT = g.mt, NT = g.nt;
     int q = blockIdx.x;
@@ -796,6 +812,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
                                                                                     uint16_t *o_pack, int m_tiles) {
     extern __shared__ float lds[];                    // WAVES/2 merge slots: 64 accumulator registers + max + sum per lane
     SEV_TRACE_T(tr0);
+    SEV_ARGS_NOW("s"(q_planes), "s"(p.it_a), "s"(p.it_b), "s"(p.it_pages), "s"(p.row_anc), "s"(g.pool), "s"(att_o), "s"(att_ml), "s"(o_pack));
     const int item = blockIdx.x, kvh = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar: loop bounds stay uniform
     // everything the block needs to know comes from two 16-byte loads and one page-id load, all independent
@@ -938,6 +955,10 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     for (int i = 0; i + 1 < my_pairs; ++i) pair_step(i, std::true_type{});
     if (my_pairs > 0) pair_step(my_pairs - 1, std::false_type{});
     SEV_TRACE_T(tr2);
+#ifdef SEV_TRACE
+    __shared__ unsigned long long wave_t2[8];
+    if (lane == 0) wave_t2[wave] = tr2;
+#endif
 
     // ---- merge the waves pairwise through LDS, in the accumulators' own register layout (a binary
     // tree: wave w + stride -> wave w); wave 0 ends up with the block's result.
@@ -976,6 +997,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
         if (wave % (2 * stride) == 0) take(wave / (2 * stride));
         __syncthreads();
     }
+    SEV_TRACE_T(tr3);
     if (wave == 0) {
         const float l = lrun + __shfl_xor(lrun, 32);
         // register 4j + r of tile t is dim 32t + 8j + 4*half + r of this lane's query
@@ -1014,8 +1036,10 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
         if (i_ < g_trace_cap) {
             unsigned long long *t_ = g_trace + (size_t)i_ * 8;
             t_[0] = 100; t_[1] = blockIdx.x | ((unsigned long long)blockIdx.y << 32);
-            t_[2] = (unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11));
-            t_[3] = tr0; t_[4] = tr1; t_[5] = tr2; t_[6] = tr_e; t_[7] = npages;
+            t_[2] = tr3 - tr1;
+            unsigned long long lo_ = ~0ull, hi_ = 0;
+            for (int w = 0; w < WAVES; ++w) { lo_ = wave_t2[w] < lo_ ? wave_t2[w] : lo_; hi_ = wave_t2[w] > hi_ ? wave_t2[w] : hi_; }
+            t_[3] = tr0; t_[4] = tr1; t_[5] = tr2; t_[6] = tr_e; t_[7] = npages | ((lo_ - tr1) << 16) | ((hi_ - tr1) << 40);
         }
     }
 #endif
