@@ -553,6 +553,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         for (int b = 0; b < MT; ++b)
 #pragma unroll
             for (int pl = 0; pl < 2; ++pl) xf[ks][b][pl] = xs[((ks * MT + b) * 2 + pl) * 64 + lane];
+    __syncthreads();                                    // stage 0 overwrites buffer 0 early: every wave must have read its X(0) fragments
 
     // One group of PF stages.  The last group of a slice issues no global loads: what it would
     // prefetch lies beyond the slice, and the epilogue would have to wait for those loads to return
