@@ -2,7 +2,7 @@
 the largest batch (256 requests of one draft token), the longest chain (64 draft tokens in one
 request), prefixes that end exactly on and right after a page boundary, a one-token prefix, rollback
 followed by a second verify, and a fork (a block with several roots).  Same tolerances as the other
-bf16 tests (the benchmark spec's 3e-2 / 3e-3; integers exact where the oracle's decisions are firm)."""
+bf16 tests (logits max-abs 3e-2, mean-abs 3e-3; integers exact where the oracle's decisions are firm)."""
 import numpy as np
 import pytest
 import torch

@@ -1,6 +1,6 @@
 """GPU parity of the bfloat16 (matrix-core) path on a small model with the large shapes' head
 geometry (GQA 4:1, head_dim 128, paged bf16 KV): chains, ragged chains, trees, long prefixes that
-span several KV chunks, more than 128 rows, multi-round commit.  Tolerances are the benchmark spec's:
+span several KV chunks, more than 128 rows, multi-round commit.  Tolerances are the ones fixed for the bfloat16 path:
 logits max-abs 3e-2 and mean-abs 3e-3 against the float32 oracle; accept/bonus/path bit-exact
 unless an arg-max the oracle relied on has a top-1/top-2 gap below 0.05."""
 import numpy as np

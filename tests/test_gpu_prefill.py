@@ -67,7 +67,7 @@ def test_prefill_bf16_then_verify():
         rounding differ by about 1e-4 of the row scale.  Hence: one bf16 step of the entry plus 1e-3 of the
         tensor's rms (entries far smaller than the row scale carry the absolute error), and at most 12 % of
         the entries differing at all.  The bar that matters, the logits of a verify on top of this cache, is
-        checked below with the benchmark spec's tolerances."""
+        checked below with the logit tolerances of the bfloat16 path."""
         err = np.abs(got - ref)
         tol = np.abs(ref) * 2.0 ** -7 + 1e-3 * float(np.sqrt(np.mean(ref * ref)))
         bad = int(np.sum(err > tol))
