@@ -811,7 +811,7 @@ template <int WAVES, bool DIRECT>
 __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g, int layer, int Hq,
                                                                                     float *att_o, float2 *att_ml, float scale_log2e,
                                                                                     uint16_t *o_pack, int m_tiles) {
-    extern __shared__ float lds[];                    // WAVES/2 merge slots: 64 accumulator registers + max + sum per lane
+    extern __shared__ float lds[];                    // WAVES merge slots: 64 accumulator registers + max + sum per lane
     SEV_TRACE_T(tr0);
     SEV_ARGS_NOW("s"(q_planes), "s"(p.it_a), "s"(p.it_b), "s"(p.it_pages), "s"(p.row_anc), "s"(g.pool), "s"(att_o), "s"(att_ml), "s"(o_pack));
     const int item = blockIdx.x, kvh = blockIdx.y;
@@ -961,73 +961,61 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     if (lane == 0) wave_t2[wave] = tr2;
 #endif
 
-    // ---- merge the waves pairwise through LDS, in the accumulators' own register layout (a binary
-    // tree: wave w + stride -> wave w); wave 0 ends up with the block's result.
-    f32x4 *slotO = (f32x4 *)lds;                        // [WAVES/2 slots][16 register quads][64 lanes]
-    float *slotM = lds + (WAVES / 2) * 64 * 64;         // [slots][64 lanes] (max), then the same for sums
-    float *slotL = slotM + (WAVES / 2) * 64;
-    auto put = [&](int sl_) {
-        slotM[sl_ * 64 + lane] = mrun;
-        slotL[sl_ * 64 + lane] = lrun;
+    // ---- merge the waves through LDS in one step: every wave publishes its (max, sum, O) in the
+    // accumulators' own register layout; then wave w reduces register quads [w * QW, (w + 1) * QW) of all
+    // waves (a quad = 4 consecutive dims of the lane's query) and stores them, so that the reduction and
+    // the stores are spread over the whole block.
+    f32x4 *slotO = (f32x4 *)lds;                        // [WAVES][16 register quads][64 lanes]
+    float *slotM = lds + WAVES * 16 * 64 * 4;           // [WAVES][64 lanes] (max), then the same for sums
+    float *slotL = slotM + WAVES * 64;
+    slotM[wave * 64 + lane] = mrun;
+    slotL[wave * 64 + lane] = lrun;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                slotO[(sl_ * 16 + t * 4 + j) * 64 + lane] = (f32x4){oacc[t][4 * j], oacc[t][4 * j + 1], oacc[t][4 * j + 2], oacc[t][4 * j + 3]};
-    };
-    auto take = [&](int sl_) {
-        const float mo = slotM[sl_ * 64 + lane], lo_ = slotL[sl_ * 64 + lane];
-        const float mnew = fmaxf(mrun, mo);
-        const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-        const float sa = exp2f(mrun - muse), sb = exp2f(mo - muse);
-        mrun = mnew;
-        lrun = lrun * sa + lo_ * sb;
+        for (int j = 0; j < 4; ++j)
+            slotO[(wave * 16 + t * 4 + j) * 64 + lane] = (f32x4){oacc[t][4 * j], oacc[t][4 * j + 1], oacc[t][4 * j + 2], oacc[t][4 * j + 3]};
+    __syncthreads();
+    float mall = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+    for (int v = 0; v < WAVES; ++v) mall = fmaxf(mall, slotM[v * 64 + lane]);
+    const float mfin = (mall == -INFINITY) ? 0.f : mall;
+    float wsc[WAVES];
+    float l = 0.f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const f32x4 o = slotO[(sl_ * 16 + t * 4 + j) * 64 + lane];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) oacc[t][4 * j + r] = oacc[t][4 * j + r] * sa + o[r] * sb;
-            }
-    };
-#pragma unroll
-    for (int stride = 1; stride < WAVES; stride *= 2) {
-        if (wave % (2 * stride) == stride) put(wave / (2 * stride));
-        __syncthreads();
-        if (wave % (2 * stride) == 0) take(wave / (2 * stride));
-        __syncthreads();
+    for (int v = 0; v < WAVES; ++v) {
+        wsc[v] = __builtin_amdgcn_exp2f(slotM[v * 64 + lane] - mfin);
+        l += slotL[v * 64 + lane] * wsc[v];
     }
+    l += __shfl_xor(l, 32);                             // the other half of the row's keys
     SEV_TRACE_T(tr3);
-    if (wave == 0) {
-        const float l = lrun + __shfl_xor(lrun, 32);
-        // register 4j + r of tile t is dim 32t + 8j + 4*half + r of this lane's query
+    constexpr int QW = 16 / WAVES;
+    const float inv = DIRECT ? 1.0f / l : 1.0f;
+    const size_t base = ((size_t)item * g.Hkv + kvh) * 32;
+    if (!DIRECT && wave == 0 && half == 0) att_ml[base + qrow] = make_float2(mall, l);
+#pragma unroll
+    for (int qi = 0; qi < QW; ++qi) {
+        const int q = wave * QW + qi;                   // register quad: dims 32 (q / 4) + 8 (q % 4) + 4 half .. +3 of this lane's query
+        f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int v = 0; v < WAVES; ++v) {
+            const f32x4 x = slotO[(v * 16 + q) * 64 + lane];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] += x[r] * wsc[v];
+        }
+        const int dim = 32 * (q >> 2) + 8 * (q & 3) + 4 * half;
         if constexpr (DIRECT) {
             // the block saw the whole sequence: normalise and write hi/lo fragments for the O projection
             if (row_live) {
-                const float inv = 1.0f / l;
-                const int m = row0 + node, k0 = (kvh * G + hg) * 128 + 4 * half;
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        uint32_t hi[2], lo[2];
-                        split_pack2(oacc[t][4 * j] * inv, oacc[t][4 * j + 1] * inv, hi[0], lo[0]);
-                        split_pack2(oacc[t][4 * j + 2] * inv, oacc[t][4 * j + 3] * inv, hi[1], lo[1]);
-                        const int kk = k0 + t * 32 + 8 * j;
-                        *(uint2 *)(o_pack + xpack_index(m, kk, 0, m_tiles)) = make_uint2(hi[0], hi[1]);
-                        *(uint2 *)(o_pack + xpack_index(m, kk, 1, m_tiles)) = make_uint2(lo[0], lo[1]);
-                    }
+                uint32_t hi[2], lo[2];
+                split_pack2(o[0] * inv, o[1] * inv, hi[0], lo[0]);
+                split_pack2(o[2] * inv, o[3] * inv, hi[1], lo[1]);
+                const int m = row0 + node, kk = (kvh * G + hg) * 128 + dim;
+                *(uint2 *)(o_pack + xpack_index(m, kk, 0, m_tiles)) = make_uint2(hi[0], hi[1]);
+                *(uint2 *)(o_pack + xpack_index(m, kk, 1, m_tiles)) = make_uint2(lo[0], lo[1]);
             }
         } else {
-            const size_t base = ((size_t)item * g.Hkv + kvh) * 32;
-            if (half == 0) att_ml[base + qrow] = make_float2(mrun, l);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *(float4 *)(att_o + (base + qrow) * 128 + t * 32 + 8 * j + 4 * half) =
-                        make_float4(oacc[t][4 * j], oacc[t][4 * j + 1], oacc[t][4 * j + 2], oacc[t][4 * j + 3]);
+            *(float4 *)(att_o + (base + qrow) * 128 + dim) = make_float4(o[0], o[1], o[2], o[3]);
         }
     }
 #ifdef SEV_TRACE
@@ -1211,11 +1199,11 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         {
             Prof p(kv, st, PROF_ATTN);
             if (att_direct) {                            // one block of 8 waves per (request, row group, KV head): no chunks, no merge
-                const size_t lds = (size_t)(4 * 64 * 64 + 2 * 4 * 64) * 4;
+                const size_t lds = (size_t)(8 * 64 * 64 + 2 * 8 * 64) * 4;      // 8 merge slots
                 hipLaunchKernelGGL((attn_bf16_kernel<8, true>), dim3(n_items, d.n_kv_heads), dim3(512), lds, st, qp, rows, kv->plan,
                                    g, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
             } else {
-                const size_t lds = (size_t)(2 * 64 * 64 + 2 * 2 * 64) * 4;   // two merge slots
+                const size_t lds = (size_t)(4 * 64 * 64 + 2 * 4 * 64) * 4;   // 4 merge slots
                 hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan,
                                    g, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
                 hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
