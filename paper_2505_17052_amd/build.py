@@ -8,7 +8,10 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsev.so")
 SOURCES = ["sev_api.hip", "kernels_common.hip", "kernels_f32.hip", "kernels_bf16.hip", "sev_sched.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result"]
+         "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result",
+         # the first 16 dwords of a kernel's scalar arguments arrive in registers at wave launch (no scalar load of
+         # the argument block on the critical path of the prologue); kernels list what they need first in front
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def build(verbose: bool = False) -> str:

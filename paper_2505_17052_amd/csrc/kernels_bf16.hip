@@ -437,8 +437,15 @@ extern "C" int sev_trace_read(unsigned long long *host, int cap) {
 // all of those fetches start together.
 #define SEV_ARGS_NOW(...) asm volatile("" : : __VA_ARGS__)
 
+// The arguments the prologue needs first (pointers and grid decomposition) are passed as leading
+// scalars as well: the library is built with kernel-argument preloading, which hands the first 16
+// dwords of the argument block to the wave in registers at launch, so the first loads can be issued
+// without waiting for a scalar load of the argument block.
 template <int MT, int NT, int EPI, int PF>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const uint4 *X_, int n_tiles_, int k_steps_, int m_tiles_total_,
+                                                        int col_groups_, int m_blocks_, int splits_, GemmArgs g) {
+    g.W = W_; g.X = X_; g.n_tiles = n_tiles_; g.k_steps = k_steps_; g.m_tiles_total = m_tiles_total_;
+    g.col_groups = col_groups_; g.m_blocks = m_blocks_; g.splits = splits_;
     // a pipeline stage is KS k-steps of 16: two for the narrow tiles, one for NT = 4 (same 32 MFMAs per wave with MT = 4)
     constexpr int KS = NT == 4 ? 1 : 2;
     constexpr int XI = KS * MT / 2;                     // 16-byte activation loads per thread and stage
@@ -447,9 +454,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     __shared__ float red[4][128];
     SEV_TRACE_T(tr0);
     constexpr int STAGE_U4 = KS * MT * 2 * 64;          // uint4 per stage
-    if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.W), "s"(g.ssq_in), "s"(g.row_cs), "s"(g.q_planes));
-    else if constexpr (EPI == EPI_ARGMAX) SEV_ARGS_NOW("s"(g.W), "s"(g.ssq_in), "s"(g.lm_val), "s"(g.logits));
-    else SEV_ARGS_NOW("s"(g.W), "s"(g.ssq_in), "s"(g.act));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // Block index decode, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, each with its
     // own L2.  Blocks that share weight tiles (the row blocks of one column group) get ids 8 apart,
@@ -545,6 +549,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
             xs[STAGE_U4 + threadIdx.x + 256 * i] = (1 < n) ? x1[i] : zero4;
         }
     }
+    // the rest of the argument block (epilogue pointers): fetched now, behind the first loads
+    if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.row_cs), "s"(g.q_planes));
+    else if constexpr (EPI == EPI_ARGMAX) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.lm_val), "s"(g.logits));
+    else SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.act));
     __syncthreads();
     SEV_TRACE_T(tr1);
 #pragma unroll
@@ -708,10 +716,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 // Split-K fix-up: block (column group cg, row tile mt, a) of 4 waves; wave w sums the S slices of the
 // 32x32 tile (column tile (cg*4 + w)*NT + a, row tile mt) in slice order and runs its epilogue.
 template <int EPI>
-__global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g) {
+__global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, const void *pa_, const void *pb_, const unsigned long long *ssq_in_,
+                                                         int col_groups_, int m_blocks_, int geo_, int n_tiles_, int M_, int N_, int heads_,
+                                                         GemmArgs g) {
     __shared__ float red[4][128];
-    if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.row_cs), "s"(g.q_planes));
-    else SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.act));
+    // leading scalars (preloaded at wave launch): everything the first loads need; pa_ / pb_ are the residual stream and
+    // the gains (EPI_RESID) or the rotary table and the rows' cache locations (EPI_QKV); geo_ = MT | NT << 8 | S << 16,
+    // heads_ = query heads | KV heads << 16
+    g.part = const_cast<float *>(part_); g.ssq_in = ssq_in_; g.col_groups = col_groups_; g.m_blocks = m_blocks_;
+    g.mt = geo_ & 255; g.nt = (geo_ >> 8) & 255; g.splits = geo_ >> 16; g.n_tiles = n_tiles_; g.M = M_; g.N = N_;
+    g.Hq = heads_ & 0xffff; g.Hkv = heads_ >> 16;
+    if constexpr (EPI == EPI_RESID) { g.h = (float *)const_cast<void *>(pa_); g.gain = (const float *)pb_; }
+    if constexpr (EPI == EPI_QKV) { g.row_cs = (const float2 *)pa_; g.row_kvloc = (const int32_t *)pb_; }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int MT = g.mt, NT = g.nt;
     int q = blockIdx.x;
@@ -741,6 +757,10 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(GemmArgs g) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     v[u][j] = src[(size_t)min(s0 + u, g.splits - 1) * slice_stride + j * 64];
+            if (s0 == 0) {                                      // the rest of the argument block, behind the first loads
+                if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.q_planes), "s"(g.k_layer), "s"(g.inv_d));
+                else SEV_ARGS_NOW("s"(g.xout), "s"(g.ssq_out), "s"(g.act), "s"(g.inv_d));
+            }
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (s0 + u < g.splits) {
@@ -808,12 +828,20 @@ __global__ __launch_bounds__(256) void lm_reduce_kernel(const float *val, const 
 // to a row iff bit j of the row's ancestor mask is set.
 // ---------------------------------------------------------------------------
 template <int WAVES, bool DIRECT>
-__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kernel(const uint16_t *q_planes, int M, DevPlan p, KvGeom g, int layer, int Hq,
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kernel(const int4 *it_a_, const int4 *it_b_, const int32_t *it_pages_,
+                                                                                    const uint16_t *q_planes, char *pool_, size_t layer_off_, size_t v_off_,
+                                                                                    int M, int heads_,
+                                                                                    DevPlan p, KvGeom g, int layer,
                                                                                     float *att_o, float2 *att_ml, float scale_log2e,
                                                                                     uint16_t *o_pack, int m_tiles) {
+    // (leading scalars: preloaded at wave launch; layer_off_ = layer * layer stride of the pool, v_off_ = offset of the
+    // V pages, heads_ = query heads | KV heads << 16)
+    p.it_a = const_cast<int4 *>(it_a_); p.it_b = const_cast<int4 *>(it_b_); p.it_pages = const_cast<int32_t *>(it_pages_);
+    const int Hq = heads_ & 0xffff;
+    g.Hkv = heads_ >> 16;
+    g.v_offset = v_off_;
     extern __shared__ float lds[];                    // WAVES merge slots: 64 accumulator registers + max + sum per lane
     SEV_TRACE_T(tr0);
-    SEV_ARGS_NOW("s"(q_planes), "s"(p.it_a), "s"(p.it_b), "s"(p.it_pages), "s"(p.row_anc), "s"(g.pool), "s"(att_o), "s"(att_ml), "s"(o_pack));
     const int item = blockIdx.x, kvh = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar: loop bounds stay uniform
     // everything the block needs to know comes from two 16-byte loads and one page-id load, all independent
@@ -833,8 +861,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     // K fragment of k-step ks: lane (key = lane % 32 -> page (key / 16), token key % 16; dims 16 ks + 8 half .. +7)
     //   byte offset in the page block: ((2 ks + half) * 16 + token) * 16
     // V fragment of (dim tile dt, page): lane (dim = lane % 32, half) -> 16 bytes at ((dt * 64 + lane) * 16)
-    const char *Kl = g.pool + (size_t)layer * g.layer_stride + (size_t)kvh * 4096 + (half * 16 + (lane & 15)) * 16;
-    const char *Vl = g.pool + (size_t)layer * g.layer_stride + g.v_offset + (size_t)kvh * 4096 + lane * 16;
+    const char *Kl = pool_ + layer_off_ + (size_t)kvh * 4096 + (half * 16 + (lane & 15)) * 16;
+    const char *Vl = pool_ + layer_off_ + g.v_offset + (size_t)kvh * 4096 + lane * 16;
     const int kpage_sel = (lane >> 4) & 1;             // which page of the pair this lane's key belongs to
 
     // K and V fragments of one page pair live in registers; the keys of the next pair are requested as
@@ -857,6 +885,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     };
     load_k(0);                                             // padded page list: always a valid page, even for an idle wave
     load_v(0);
+    SEV_ARGS_NOW("s"(p.row_anc), "s"(p.causal), "s"(att_o), "s"(att_ml), "s"(o_pack));   // the rest of the argument block, behind the first loads
 
     // query fragments of this lane's row (hi and lo planes, 8 k-steps): 64 registers for the whole chunk
     const int R = rg * 32 + qrow;
@@ -1137,7 +1166,8 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     dim3 grid((unsigned)(g8 * ga.m_blocks * ga.splits));
     const size_t lds = (size_t)2 * (c.NT == 4 ? 1 : 2) * c.MT * 2 * 64 * 16;
 #define SEV_LAUNCH(MT_, NT_, PF_)                                                                                     \
-    hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, PF_>), grid, dim3(256), lds, st, ga)
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, PF_>), grid, dim3(256), lds, st, ga.W, ga.X, ga.n_tiles, ga.k_steps,         \
+                       ga.m_tiles_total, ga.col_groups, ga.m_blocks, ga.splits, ga)
 #define SEV_BY_NT(MT_, PF_)                                                                                           \
     do {                                                                                                              \
         if (c.NT == 2) SEV_LAUNCH(MT_, 2, PF_); else SEV_LAUNCH(MT_, 1, PF_);                                         \
@@ -1151,7 +1181,9 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     if constexpr (EPI != EPI_ARGMAX) {
         if (c.S > 1)
             hipLaunchKernelGGL((gemm_fixup_kernel<EPI>), dim3((unsigned)(ga.col_groups * ga.m_blocks * c.MT * c.NT)), dim3(256), 0,
-                               st, ga);
+                               st, (const float *)ga.part, EPI == EPI_QKV ? (const void *)ga.row_cs : (const void *)ga.h,
+                               EPI == EPI_QKV ? (const void *)ga.row_kvloc : (const void *)ga.gain, ga.ssq_in, ga.col_groups, ga.m_blocks,
+                               ga.mt | (ga.nt << 8) | (ga.splits << 16), ga.n_tiles, ga.M, ga.N, ga.Hq | (ga.Hkv << 16), ga);
     }
 }
 
@@ -1200,12 +1232,12 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             Prof p(kv, st, PROF_ATTN);
             if (att_direct) {                            // one block of 8 waves per (request, row group, KV head): no chunks, no merge
                 const size_t lds = (size_t)(8 * 64 * 64 + 2 * 8 * 64) * 4;      // 8 merge slots
-                hipLaunchKernelGGL((attn_bf16_kernel<8, true>), dim3(n_items, d.n_kv_heads), dim3(512), lds, st, qp, rows, kv->plan,
-                                   g, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
+                hipLaunchKernelGGL((attn_bf16_kernel<8, true>), dim3(n_items, d.n_kv_heads), dim3(512), lds, st, kv->plan.it_a, kv->plan.it_b,
+                                   kv->plan.it_pages, qp, g.pool, (size_t)l * g.layer_stride, g.v_offset, rows, d.n_q_heads | (d.n_kv_heads << 16), kv->plan, g, l, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
             } else {
                 const size_t lds = (size_t)(4 * 64 * 64 + 2 * 4 * 64) * 4;   // 4 merge slots
-                hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(n_items, d.n_kv_heads), dim3(256), lds, st, qp, rows, kv->plan,
-                                   g, l, d.n_q_heads, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
+                hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(n_items, d.n_kv_heads), dim3(256), lds, st, kv->plan.it_a, kv->plan.it_b,
+                                   kv->plan.it_pages, qp, g.pool, (size_t)l * g.layer_stride, g.v_offset, rows, d.n_q_heads | (d.n_kv_heads << 16), kv->plan, g, l, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
                 hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
                                    kv->plan, d.n_q_heads, d.n_kv_heads, op, m_tiles);
             }
