@@ -1065,28 +1065,50 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
 
 // cross-chunk merge + normalisation; writes the attention output as hi/lo fragments for the O projection.
 // grid (merge groups, Hkv), 256 threads: thread owns (row q = t/8, 16 dims).
-__global__ __launch_bounds__(256) void attn_merge_kernel(const float *att_o, const float2 *att_ml, DevPlan p, int Hq, int Hkv,
-                                                         uint16_t *o_pack, int m_tiles) {
+__global__ __launch_bounds__(256) void attn_merge_kernel(const int4 *mg_rec, const float *att_o, const float2 *att_ml, uint16_t *o_pack,
+                                                         int Hq, int Hkv, int m_tiles) {
+    // (all arguments are scalars: preloaded at wave launch; one 16-byte record describes the group)
     const int grpi = blockIdx.x, kvh = blockIdx.y;
-    const int b = p.mg_req[grpi], rg = p.mg_rg[grpi], item0 = p.mg_item0[grpi], cnt = p.mg_count[grpi];
-    const int n = p.req_n[b], row0 = p.req_row0[b], G = Hq / Hkv;
+    const int4 rec = mg_rec[grpi];
+    const int rg = rec.x & 0xffff, cnt = rec.x >> 16, item0 = rec.y, n = rec.z, row0 = rec.w, G = Hq / Hkv;
     const int q = threadIdx.x >> 3, d0 = (threadIdx.x & 7) * 16;
     const int R = rg * 32 + q;
     if (R >= G * n) return;
     const int hg = R / n, node = R - hg * n;
-    float mg = -INFINITY;
-    for (int c = 0; c < cnt; ++c) mg = fmaxf(mg, att_ml[((size_t)(item0 + c) * Hkv + kvh) * 32 + q].x);
-    float acc[16], l = 0.f;
+    // chunks are combined four at a time with a running maximum: all loads of a batch are issued together
+    // (a group rarely has more than four chunks, so the kernel is one round of loads deep)
+    float mg = -INFINITY, l = 0.f, acc[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-    for (int c = 0; c < cnt; ++c) {
-        const size_t base = ((size_t)(item0 + c) * Hkv + kvh) * 32 + q;
-        const float2 ml = att_ml[base];
-        const float sc = exp2f(ml.x - mg);
-        l += sc * ml.y;
-        const float *o = att_o + base * 128 + d0;
+    for (int c0 = 0; c0 < cnt; c0 += 4) {
+        float2 ml[4];
+        float4 o[4][4];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] += sc * o[e];
+        for (int u = 0; u < 4; ++u) {
+            const size_t base = ((size_t)(item0 + min(c0 + u, cnt - 1)) * Hkv + kvh) * 32 + q;
+            ml[u] = att_ml[base];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[u][e] = *(const float4 *)(att_o + base * 128 + d0 + 4 * e);
+        }
+        float mb = mg;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) mb = (c0 + u < cnt) ? fmaxf(mb, ml[u].x) : mb;
+        const float muse = (mb == -INFINITY) ? 0.f : mb;
+        const float keep = exp2f(mg - muse);
+        l *= keep;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] *= keep;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float sc = (c0 + u < cnt) ? exp2f(ml[u].x - muse) : 0.f;
+            l += sc * ml[u].y;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[4 * e] += sc * o[u][e].x; acc[4 * e + 1] += sc * o[u][e].y;
+                acc[4 * e + 2] += sc * o[u][e].z; acc[4 * e + 3] += sc * o[u][e].w;
+            }
+        }
+        mg = mb;
     }
     const float inv = 1.0f / l;
 #pragma unroll
@@ -1238,8 +1260,8 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
                 const size_t lds = (size_t)(4 * 64 * 64 + 2 * 4 * 64) * 4;   // 4 merge slots
                 hipLaunchKernelGGL((attn_bf16_kernel<4, false>), dim3(n_items, d.n_kv_heads), dim3(256), lds, st, kv->plan.it_a, kv->plan.it_b,
                                    kv->plan.it_pages, qp, g.pool, (size_t)l * g.layer_stride, g.v_offset, rows, d.n_q_heads | (d.n_kv_heads << 16), kv->plan, g, l, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles);
-                hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, kv->att_o, kv->att_ml,
-                                   kv->plan, d.n_q_heads, d.n_kv_heads, op, m_tiles);
+                hipLaunchKernelGGL(attn_merge_kernel, dim3(n_groups, d.n_kv_heads), dim3(256), 0, st, (const int4 *)kv->plan.mg_rec,
+                                   (const float *)kv->att_o, (const float2 *)kv->att_ml, op, d.n_q_heads, d.n_kv_heads, m_tiles);
             }
         }
         {   // output projection; residual add, FFN-norm operand and scale in its epilogue

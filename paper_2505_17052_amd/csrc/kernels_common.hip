@@ -111,10 +111,7 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
         const int cpp = (pages + my_chunks - 1) / my_chunks;
         int it = s_item0[t], g0 = s_grp0[t];
         for (int rg = 0; rg < my_groups; ++rg) {
-            d.p.mg_req[g0 + rg] = t;
-            d.p.mg_rg[g0 + rg] = rg;
-            d.p.mg_item0[g0 + rg] = it;
-            d.p.mg_count[g0 + rg] = my_chunks;
+            d.p.mg_rec[g0 + rg] = make_int4(rg | (my_chunks << 16), it, n, row0);
             for (int c = 0; c < my_chunks; ++c, ++it) {
                 const int p0 = c * cpp;
                 d.p.it_a[it] = make_int4(rg, p0, min(cpp, pages - p0), P);

@@ -308,11 +308,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->plan.it_a = (int4 *)(w + o_it);
     kv->plan.it_b = kv->plan.it_a + kv->max_items;
     kv->plan.it_pages = (int32_t *)(kv->plan.it_b + kv->max_items);
-    int32_t *mg = (int32_t *)(w + o_mg);
-    kv->plan.mg_req = mg;
-    kv->plan.mg_rg = mg + kv->max_groups;
-    kv->plan.mg_item0 = mg + 2 * (size_t)kv->max_groups;
-    kv->plan.mg_count = mg + 3 * (size_t)kv->max_groups;
+    kv->plan.mg_rec = (int4 *)(w + o_mg);
     kv->h = (float *)(w + o_h);
     kv->part = (float *)(w + o_part);
     kv->xa = w + o_xa;

@@ -73,7 +73,7 @@ struct DevPlan {
     // b = {draft nodes, first row, request, 0}; pages = physical page ids of the chunk, SEV_ATT_MAX_CP per item
     int4 *it_a, *it_b;
     int32_t *it_pages;
-    int32_t *mg_req, *mg_rg, *mg_item0, *mg_count;         // [merge groups]
+    int4 *mg_rec;             // [merge groups] {row group | chunks << 16, first work item, draft nodes, first row}
     int causal;               // 1: blocks are chains (node i sees nodes <= i; any length), 0: trees (ancestor masks, <= 64 nodes)
 };
 
