@@ -242,13 +242,13 @@ struct TilePre {
     int kvloc;               // EPI_QKV: physical page * 16 + token in page of the row's cache position
 };
 
-template <int EPI>
-__device__ __forceinline__ TilePre tile_pre(const GemmArgs &g, int T, int m, int nsub) {
+template <int EPI, bool RS_KNOWN = false>
+__device__ __forceinline__ TilePre tile_pre(const GemmArgs &g, int T, int m, int nsub, float rs_known = 1.0f) {
     TilePre p;
-    p.rs = 1.0f;
+    p.rs = rs_known;
     p.kvloc = 0;
     if (m >= g.M) return p;
-    if (g.ssq_in) p.rs = rms_scale(g.ssq_in[m], g.inv_d, g.eps);
+    if (!RS_KNOWN && g.ssq_in) p.rs = rms_scale(g.ssq_in[m], g.inv_d, g.eps);
     if constexpr (EPI == EPI_RESID) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -549,6 +549,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
             xs[STAGE_U4 + threadIdx.x + 256 * i] = (1 < n) ? x1[i] : zero4;
         }
     }
+    // a block that runs the epilogue itself fetches its rows' sums of squares now, so that the row scales are
+    // there when the loop ends
+    unsigned long long sq_rows[MT];
+#pragma unroll
+    for (int b = 0; b < MT; ++b) {
+        const int m = (mt0 + b) * 32 + mrow;
+        sq_rows[b] = (g.splits == 1 && g.ssq_in && m < g.M) ? g.ssq_in[m] : 0ull;
+    }
     // the rest of the argument block (epilogue pointers): fetched now, behind the first loads
     if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.row_cs), "s"(g.q_planes));
     else if constexpr (EPI == EPI_ARGMAX) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.lm_val), "s"(g.logits));
@@ -659,10 +667,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
         for (int b = 0; b < MT; ++b) {
             ss[b] = 0.f;
             const int m = (mt0 + b) * 32 + mrow;
+            const float rs_b = g.ssq_in ? rms_scale(sq_rows[b], g.inv_d, g.eps) : 1.0f;
 #pragma unroll
             for (int a = 0; a < NT; ++a)
                 if (tile0 + a < g.n_tiles) {
-                    const TilePre pre = tile_pre<EPI>(g, tile0 + a, m, nsub);
+                    const TilePre pre = tile_pre<EPI, true>(g, tile0 + a, m, nsub, rs_b);
                     ss[b] += tile_epilogue<EPI>(g, acc[a][b], tile0 + a, m, nsub, pre);
                 }
         }
@@ -680,7 +689,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
 #pragma unroll
         for (int b = 0; b < MT; ++b) {
             const int m = (mt0 + b) * 32 + mrow;
-            const float rsb = (g.logits && g.ssq_in && m < g.M) ? rms_scale(g.ssq_in[m], g.inv_d, g.eps) : 1.0f;
+            const float rsb = (g.logits && g.ssq_in && m < g.M) ? rms_scale(sq_rows[b], g.inv_d, g.eps) : 1.0f;
             float bv = -INFINITY;
             int bi = 0x7fffffff;
 #pragma unroll
