@@ -137,7 +137,7 @@ def main():
     tokens = B * k
     # HBM bytes per gate/up launch from the rocprofv3 FETCH_SIZE and WRITE_SIZE runs kept under profiles/
     # (KiB per dispatch x the factor a plain 1 GiB copy gives each counter); they hold for this one launch shape
-    traffic = (124041.1 * 2.0 + 7168.0 * 1.0) * 1024.0 if (wl.name == "8b-chain-b16k8" and not os.environ.get("SEV_TUNE_GU")) else None
+    traffic = (123017.5 * 2.0 + 7168.0 * 1.0) * 1024.0 if (wl.name == "8b-chain-b16k8" and not os.environ.get("SEV_TUNE_GU")) else None
     out = {
         "metric": ("verified draft tokens/sec on 1 MI355X (8B-shape bf16, B=16, k=8); % roofline" if not args.padded_kv else
                    "COMPARISON RUN (padded KV + dense mask): verified draft tokens/sec on 1 MI355X"),
