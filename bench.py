@@ -130,6 +130,16 @@ def main():
     per_class = {nm: (ms / 5.0) for nm, (ms, n) in batch.kv.profile_read().items()}
     batch.kv.profile_enable(0)
 
+    # what a pair of events reads around an empty interval on the same stream, in the middle of the same queue of
+    # kernels: the part of avg_launch_ms that is not the kernel itself (reported, not subtracted)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+    for a, b in ev:
+        step()
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    empty_ms = float(np.median([a.elapsed_time(b) for a, b in ev]))
+
     gu_bytes = 2 * shape.d_ffn * shape.d_model * 2                      # gate and up matrices, bf16, read once
     gu_avg_ms = gu_ms / max(gu_n, 1)
     achieved = gu_bytes / (gu_avg_ms * 1e-3) / 1e9
@@ -152,7 +162,7 @@ def main():
                    "padded_kv": bool(args.padded_kv), "mean_accept_len": float(accept.mean()), "precision": "bf16 weights/KV, split-bf16 activations, f32 accumulate"},
         "roofline": {"bound": "hbm", "kernel": "gemm_gate_up_swiglu", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
                      "frac": achieved / 8000.0, "traffic": traffic, "bytes_per_launch": gu_bytes,
-                     "avg_launch_ms": gu_avg_ms, "launches_timed": gu_n,
+                     "avg_launch_ms": gu_avg_ms, "launches_timed": gu_n, "empty_event_pair_ms": empty_ms,
                      "ms_per_step_with_events": (t4 - t3) * 1e3 / args.steps},
         "step_roofline": {"algorithmic_bytes_per_step": step_bytes, "achieved_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
                           "frac_of_8TBps": step_bytes / (ms_per_step * 1e-3) / 8e12,
