@@ -394,6 +394,7 @@ __device__ __forceinline__ unsigned long long sev_trace_now() {     // pinned in
     return t;
 }
 #define SEV_TRACE_T(var) const unsigned long long var = sev_trace_now()
+#define SEV_TRACE_FIX(i) trf[i] = sev_trace_now()
 extern "C" int sev_trace_begin(int cap) {
     unsigned long long *buf;
     if (hipMalloc(&buf, (size_t)cap * 64) != hipSuccess) return -1;
@@ -428,6 +429,7 @@ extern "C" int sev_trace_read(unsigned long long *host, int cap) {
     }
 #else
 #define SEV_TRACE_T(var)
+#define SEV_TRACE_FIX(i)
 #define SEV_TRACE_END(t4)
 #endif
 
@@ -729,6 +731,7 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, con
                                                          int col_groups_, int m_blocks_, int geo_, int n_tiles_, int M_, int N_, int heads_,
                                                          GemmArgs g) {
     __shared__ float red[4][128];
+    SEV_TRACE_T(tr0);
     // leading scalars (preloaded at wave launch): everything the first loads need; pa_ / pb_ are the residual stream and
     // the gains (EPI_RESID) or the rotary table and the rows' cache locations (EPI_QKV); geo_ = MT | NT << 8 | S << 16,
     // heads_ = query heads | KV heads << 16
@@ -757,6 +760,9 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, con
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const bool live = T < g.n_tiles;
     float ss = 0.f;
+#ifdef SEV_TRACE
+    unsigned long long trf[3] = {0, 0, 0};
+#endif
     if (live) {
         const TilePre pre = tile_pre<EPI>(g, T, m, nsub);       // issued ahead of the slice loads
         for (int s0 = 0; s0 < g.splits; s0 += 8) {
@@ -780,13 +786,25 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, con
                     }
                 }
         }
+        SEV_TRACE_FIX(1);
         ss = tile_epilogue<EPI>(g, acc, T, m, nsub, pre);
     }
+    SEV_TRACE_FIX(2);
     if constexpr (EPI == EPI_RESID) {
         ss += __shfl_xor(ss, 32);
         if (lane < 32) red[wave][mrow] = ss;
         ssq_commit(g, red, 32, mt * 32, cg == 0 && a == 0);
     }
+#ifdef SEV_TRACE
+    if (threadIdx.x == 0 && g_trace) {
+        SEV_TRACE_T(tr_e);
+        const unsigned i_ = atomicAdd(&g_trace_pos, 1u);
+        if (i_ < g_trace_cap) {
+            unsigned long long *t_ = g_trace + (size_t)i_ * 8;
+            t_[0] = 200 + EPI; t_[1] = blockIdx.x; t_[2] = 0; t_[3] = tr0; t_[4] = trf[1]; t_[5] = trf[2]; t_[6] = tr_e; t_[7] = g.splits;
+        }
+    }
+#endif
 }
 
 // ---------------------------------------------------------------------------
