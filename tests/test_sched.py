@@ -193,6 +193,31 @@ def test_replay_driver_matches_oracle_simulation():
         assert got == want, trial
 
 
+def test_waiting_for_a_fuller_batch_hand_case():
+    """min_batch = 3, max_wait 100: worked through by hand; the oracle and the library must both follow it."""
+    import paper_2505_17052_amd as sev
+    want = [(0, ([], 50)),                       # one block there: wait, the third one is due at 50 (before the deadline 100)
+            (50, ([(0, 2), (1, 3), (2, 1)], 50)),
+            (60, ([], 500)),                     # only a future block is queued
+            (500, ([], 600)),                    # it is alone: wait until it has waited 100
+            (599, ([], 600)),
+            (600, ([(3, 4)], 600)),
+            (601, ([], -1))]
+    for make in (lambda: so.Former(4, 16, 3, 100), lambda: sev.Scheduler(4, 16, 3, 100)):
+        f = make()
+        for r, (n, t) in enumerate([(2, 0), (3, 10), (1, 50), (4, 500)]):
+            f.submit(r, n, t)
+        for now, expect in want:
+            assert f.next_batch(now) == expect, (now, expect)
+    # the row cap stops a batch at the first block that does not fit, and nobody overtakes it
+    for make in (lambda: so.Former(4, 8), lambda: sev.Scheduler(4, 8)):
+        f = make()
+        for r, n in enumerate([5, 4, 2]):
+            f.submit(r, n, 0)
+        assert f.next_batch(0) == ([(0, 5)], 0)            # 5 + 4 > 8: block 1 waits, and block 2 does not jump the queue
+        assert f.next_batch(0) == ([(1, 4), (2, 2)], 0)
+
+
 # ---------------------------------------------------------------- edge-side draft alignment
 
 def test_oracle_edge_align_hand_cases():
