@@ -95,6 +95,46 @@ def test_config2_chain_b16_k8(setup):
     announce(f"  exact-compared {n_exact}/{B}; logits max-abs {worst:.2e} mean-abs {mean:.2e}; "
              f"accept {[r.accept_len for r in res]} ({time.time() - t:.0f}s)")
     assert n_exact >= B // 2
+    # stochastic verification (temperature 0.7) of the same block at the full shape: the oracle's accept / resample rule
+    # applied to the oracle's logits of this very block; edge distributions = perturbed copies of the server's
+    T, V = 0.7, SHAPE.vocab
+    rng = np.random.default_rng(wl.seed)
+    q = np.full((B, k, V), 1.0 / V, dtype=np.float32)
+    for b in range(B):
+        for i in range(1, k):
+            q[b, i] = vo.softmax_t(res[b].logits[i - 1] + 0.7 * rng.standard_normal(V), T)
+    u_acc = rng.random((B, k)).astype(np.float32)
+    u_emit = rng.random(B).astype(np.float32)
+    batch.kv.set_state(None, lens, [c.next_tok for c in caches])
+    outs = sev.verify_sample(model, batch.kv, lens, torch.tensor(drafts, device="cuda"), k, torch.tensor(q.reshape(B * k, V), device="cuda"),
+                             torch.tensor(u_acc, device="cuda"), torch.tensor(u_emit, device="cuda"), T)
+    torch.cuda.synchronize()
+    assert batch.kv.get_state(0)[2] == 0
+    acc_s, emi_s = outs["accept_len"].cpu().numpy(), outs["emitted_token"].cpu().numpy()
+    n_a = n_s = 0
+    for b in range(B):
+        p_rows = np.stack([vo.softmax_t(row, T) for row in res[b].logits])
+        a, tok, m_acc, m_emit = vo.accept_sample_chain(drafts[b], caches[b].next_tok, p_rows, q[b].astype(np.float64), u_acc[b], float(u_emit[b]))
+        if m_acc > 3e-2:                          # every acceptance test of the request is firm (up to 7 tests per request)
+            n_a += 1
+            assert acc_s[b] == a, (b, acc_s[b], a)
+            if m_emit > 1e-4:
+                n_s += 1
+                assert emi_s[b] == tok, (b, emi_s[b], tok)
+            else:
+                # the draw lands within 1e-4 of a cell boundary (cells are ~1e-5 wide at this vocabulary): any token whose
+                # cell lies within 1e-3 of the drawn point is a valid answer
+                if a == 0:
+                    assert emi_s[b] == tok
+                    continue
+                w = p_rows[a - 1] if a == k else np.maximum(p_rows[a - 1] - q[b, a].astype(np.float64), 0.0)
+                cdf = np.cumsum(w) / w.sum()
+                g_tok = int(emi_s[b])
+                lo_edge = cdf[g_tok - 1] if g_tok > 0 else 0.0
+                assert lo_edge - 1e-3 <= float(u_emit[b]) <= cdf[g_tok] + 1e-3, (b, g_tok, tok, lo_edge, cdf[g_tok], float(u_emit[b]))
+    announce(f"  stochastic rule on the same block: accept {acc_s.tolist()}; accept lengths compared {n_a}/{B}, emitted tokens {n_s}/{B} "
+             f"({time.time() - t:.0f}s)")
+    assert n_a >= 4 and n_s >= 3
     # the plain entry point in the benchmark's launch configuration gives the same integers
     batch.kv.set_state(None, lens, [c.next_tok for c in caches])
     a2, b2 = sev.verify(model, batch.kv, lens, torch.tensor(drafts, device="cuda"), None, B, k)
