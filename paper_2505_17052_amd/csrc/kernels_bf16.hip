@@ -581,6 +581,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
 #pragma unroll
         for (int u = 0; u < PF; ++u) {
             const int st = base + u;
+            if constexpr (!LOAD) {
+                if (st >= n) break;                     // padding of the slice (uniform): nothing left to multiply
+            }
             const u32x4 *xnext = xs + ((u + 1) & 1) * STAGE_U4 + lane;      // X(st+1)
             // X(st+2): registers -> the LDS buffer whose fragments (stage st) were read during stage st-1
             const bool live = st + 2 < n;
