@@ -307,34 +307,49 @@ __global__ void commit_state_kernel(SlotList sl, int B, int rollback, int32_t *s
 //   u_acc[c] * q_c(x) < p(x); a rejection replaces p by the normalised residual max(0, p - q_c)
 //   (the normaliser is a block-wide sum over the vocabulary, in a fixed order); an acceptance
 //   moves to c.  When no child is left the emitted token is drawn from the current p by inverse
-//   CDF in token-id order: every thread sums a contiguous range of ids, the ranges are scanned
-//   in order, and the range that holds u_emit * total is walked.  Chains are trees whose node
-//   i has parent i - 1.
+//   CDF in token-id order: sums of groups of 64 consecutive ids, a scan over the groups, then a
+//   scan inside the group that holds u_emit * total.  Chains are trees whose node i has parent
+//   i - 1.
 // ---------------------------------------------------------------------------
 #define SEV_MAX_REJ 16   // rejected siblings remembered at one node
 
 __global__ __launch_bounds__(1024) void softmax_stats_kernel(const float *logits, int vocab, float inv_t, float2 *stats) {
-    __shared__ float red[16];
+    // one pass with a running maximum (the sum is rescaled whenever the maximum grows); 16-byte loads where the
+    // row allows it; the partial (max, sum) pairs are combined in a fixed order
+    __shared__ float red_m[16], red_s[16];
     const float *row = logits + (size_t)blockIdx.x * vocab;
-    float mx = -INFINITY;
-    for (int v = threadIdx.x; v < vocab; v += 1024) mx = fmaxf(mx, row[v]);
-    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
-    __syncthreads();
-    mx = red[0];
-#pragma unroll
-    for (int w = 1; w < 16; ++w) mx = fmaxf(mx, red[w]);
-    __syncthreads();
-    float sum = 0.f;
-    for (int v = threadIdx.x; v < vocab; v += 1024) sum += expf((row[v] - mx) * inv_t);
-    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
+    float m = -INFINITY, sum = 0.f;
+    auto take = [&](float x) {
+        if (x > m) { sum *= expf((m - x) * inv_t); m = x; }       // exp(-inf) = 0 covers the first element
+        sum += expf((x - m) * inv_t);
+    };
+    const bool vec = ((vocab & 3) == 0) && ((((size_t)blockIdx.x * vocab) & 3) == 0) && ((((uintptr_t)logits) & 15) == 0);
+    if (vec) {
+        const float4 *r4 = (const float4 *)row;
+        for (int i = threadIdx.x; i < (vocab >> 2); i += 1024) {
+            const float4 x = r4[i];
+            const float mx4 = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+            if (mx4 > m) { sum *= expf((m - mx4) * inv_t); m = mx4; }
+            sum += expf((x.x - m) * inv_t) + expf((x.y - m) * inv_t) + expf((x.z - m) * inv_t) + expf((x.w - m) * inv_t);
+        }
+    } else {
+        for (int v = threadIdx.x; v < vocab; v += 1024) take(row[v]);
+    }
+    // wave, then block: (m, s) pairs merge as s = s_a * exp((m_a - m) / T) + s_b * exp((m_b - m) / T)
+    auto merge = [&](float mo, float so) {
+        const float mn = fmaxf(m, mo);
+        const float a = (m == -INFINITY) ? 0.f : expf((m - mn) * inv_t), b = (mo == -INFINITY) ? 0.f : expf((mo - mn) * inv_t);
+        sum = sum * a + so * b;
+        m = mn;
+    };
+    for (int o = 32; o > 0; o >>= 1) merge(__shfl_xor(m, o), __shfl_xor(sum, o));
+    if ((threadIdx.x & 63) == 0) { red_m[threadIdx.x >> 6] = m; red_s[threadIdx.x >> 6] = sum; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        float z = 0.f;
+        m = red_m[0]; sum = red_s[0];
 #pragma unroll
-        for (int w = 0; w < 16; ++w) z += red[w];
-        stats[blockIdx.x] = make_float2(mx, z);
+        for (int w = 1; w < 16; ++w) merge(red_m[w], red_s[w]);
+        stats[blockIdx.x] = make_float2(m, sum);
     }
 }
 
@@ -351,17 +366,35 @@ __global__ __launch_bounds__(1024) void sample_walk_kernel(DevPlan p, int k_max,
                                                            uint32_t *err, int32_t *pend_n, int32_t *pend_a, int32_t *pend_bonus,
                                                            int32_t *pend_path, int32_t *accept_len, int32_t *emitted, int32_t *path_out) {
     __shared__ WalkState s;
-    __shared__ float s_part[1024];
-    __shared__ float s_total;
+    __shared__ float s_part[16];
     __shared__ int s_pick;
-    const int b = blockIdx.x, t = threadIdx.x;
+    extern __shared__ float s_grp[];                    // [ceil(vocab / 64)] sums of 64 consecutive ids (draw pass)
+    const int b = blockIdx.x, t = threadIdx.x, wave = t >> 6, lane = t & 63;
+    const int n_groups = (vocab + 63) >> 6;
     const int slot = p.req_slot[b], n = p.req_n[b], row0 = p.req_row0[b];
-    const int32_t *tk = tokens + (size_t)b * k_max;
-    const int32_t *par = parents ? parents + (size_t)b * k_max : nullptr;
-    auto parent_of = [&](int c) {
-        const int q = par ? par[c] : c - 1;
-        return (q < -1 || q >= c) ? -1 : q;
-    };
+    // the block's tokens and (sanitised) parents in LDS, and for every node the outcome of its acceptance test
+    // against the plain softmax at its parent: the test the walk needs as long as no sibling was rejected at that
+    // parent, taken for all nodes at once instead of one after the other along the path
+    __shared__ int s_tk[SEV_MAX_DRAFT], s_par[SEV_MAX_DRAFT], s_acc0[SEV_MAX_DRAFT];
+    if (t < n) {
+        const int c = t;
+        const int q0 = parents ? parents[(size_t)b * k_max + c] : c - 1;
+        const int q = (q0 < -1 || q0 >= c) ? -1 : q0;
+        int x = tokens[(size_t)b * k_max + c];
+        if (x < 0 || x >= vocab) x = 0;                 // the embedding step has flagged it and used id 0 as well
+        s_tk[c] = x;
+        s_par[c] = q;
+        int ok = 0;
+        if (q >= 0) {
+            const float2 st = stats[row0 + q];
+            const float px = expf((logits[(size_t)(row0 + q) * vocab + x] - st.x) * inv_t) / st.y;
+            ok = u_acc[(size_t)b * k_max + c] * draft_probs[(size_t)(row0 + c) * vocab + x] < px;
+        }
+        s_acc0[c] = ok;
+    }
+    __syncthreads();
+    const int *tk = s_tk;
+    auto parent_of = [&](int c) { return s_par[c]; };
     // value at token v of the current distribution: the node's softmax, then one residual step per rejected sibling
     auto current = [&](int v) {
         const float2 st = stats[row0 + s.cur];
@@ -369,6 +402,21 @@ __global__ __launch_bounds__(1024) void sample_walk_kernel(DevPlan p, int k_max,
         for (int j = 0; j < s.nrej; ++j) r = fmaxf(r - draft_probs[(size_t)(row0 + s.rej[j]) * vocab + v], 0.f) / s.R[j];
         return r;
     };
+    // the same for four consecutive ids (16-byte loads: a block has one compute unit's worth of loads in flight, so the
+    // passes over the vocabulary are bound by how many bytes each load carries)
+    auto current4 = [&](int i) {
+        const float2 st = stats[row0 + s.cur];
+        const float4 l = ((const float4 *)(logits + (size_t)(row0 + s.cur) * vocab))[i];
+        float4 r = make_float4(expf((l.x - st.x) * inv_t) / st.y, expf((l.y - st.x) * inv_t) / st.y, expf((l.z - st.x) * inv_t) / st.y,
+                               expf((l.w - st.x) * inv_t) / st.y);
+        for (int j = 0; j < s.nrej; ++j) {
+            const float4 q = ((const float4 *)(draft_probs + (size_t)(row0 + s.rej[j]) * vocab))[i];
+            const float R = s.R[j];
+            r = make_float4(fmaxf(r.x - q.x, 0.f) / R, fmaxf(r.y - q.y, 0.f) / R, fmaxf(r.z - q.z, 0.f) / R, fmaxf(r.w - q.w, 0.f) / R);
+        }
+        return r;
+    };
+    const bool vec = ((vocab & 3) == 0) && ((((uintptr_t)logits | (uintptr_t)draft_probs) & 15) == 0);
     if (t == 0) {
         s.cur = -1;
         s.a = 0;
@@ -380,16 +428,16 @@ __global__ __launch_bounds__(1024) void sample_walk_kernel(DevPlan p, int k_max,
     __syncthreads();
     int tok = next_tok[slot];
     if (s.cur >= 0) {
-        const int per = (vocab + 1023) / 1024, v0 = t * per, v1 = min(vocab, v0 + per);
         for (int guard = 0; guard <= 2 * SEV_MAX_DRAFT; ++guard) {          // every round consumes a child or ends the walk
             if (t == 0) {
                 s.action = 2;
                 for (int c = s.child; c < n; ++c) {
                     if (parent_of(c) != s.cur) continue;
                     const int x = tk[c];
-                    const float px = current(x), qx = draft_probs[(size_t)(row0 + c) * vocab + x];
                     s.child = c + 1;
-                    if (u_acc[(size_t)b * k_max + c] * qx < px) {
+                    const bool ok = s.nrej == 0 ? s_acc0[c] != 0
+                                                : u_acc[(size_t)b * k_max + c] * draft_probs[(size_t)(row0 + c) * vocab + x] < current(x);
+                    if (ok) {
                         s.cur = c;
                         s.path[s.a++] = c;
                         s.nrej = 0;
@@ -407,62 +455,111 @@ __global__ __launch_bounds__(1024) void sample_walk_kernel(DevPlan p, int k_max,
                 __syncthreads();                                              // everyone has read the action before thread 0 writes the next one
                 continue;
             }
-            // a block-wide pass over the vocabulary: the residual against the rejected child (action 1), or the
-            // current distribution itself for the draw (action 2); range sums in id order
-            const float *qrow = action == 1 ? draft_probs + (size_t)(row0 + s.rej[s.nrej]) * vocab : nullptr;
-            float sum = 0.f;
-            for (int v = v0; v < v1; ++v) {
-                const float r = current(v);
-                sum += qrow ? fmaxf(r - qrow[v], 0.f) : r;
-            }
-            s_part[t] = sum;
-            __syncthreads();
-            if (t == 0) {
-                float tot = 0.f;
-                for (int i = 0; i < 1024; ++i) tot += s_part[i];
-                s_total = tot;
-                if (action == 1) {
+            // a block-wide pass over the vocabulary, thread t at ids t, t + 1024, ... (coalesced)
+            if (action == 1) {
+                // normaliser of the residual against the rejected child; wave sums, then the 16 wave totals in order
+                const float *qrow = draft_probs + (size_t)(row0 + s.rej[s.nrej]) * vocab;
+                float sum = 0.f;
+                if (vec) {
+#pragma unroll 2
+                    for (int i = t; i < (vocab >> 2); i += 1024) {
+                        const float4 r = current4(i), q = ((const float4 *)qrow)[i];
+                        sum += (fmaxf(r.x - q.x, 0.f) + fmaxf(r.y - q.y, 0.f)) + (fmaxf(r.z - q.z, 0.f) + fmaxf(r.w - q.w, 0.f));
+                    }
+                } else {
+                    for (int v = t; v < vocab; v += 1024) sum += fmaxf(current(v) - qrow[v], 0.f);
+                }
+                for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+                if (lane == 0) s_part[wave] = sum;
+                __syncthreads();
+                if (t == 0) {
+                    float tot = 0.f;
+                    for (int i = 0; i < 16; ++i) tot += s_part[i];
                     if (s.nrej >= SEV_MAX_REJ) atomicOr(err, 8u);           // more rejected siblings than the walk remembers
                     else if (tot > 0.f) { s.R[s.nrej] = tot; ++s.nrej; }    // an empty residual leaves the distribution as it is
                 }
+                __syncthreads();
+                continue;
+            }
+            // the draw: inverse CDF of the current distribution in token-id order.  Sums of groups of 64 consecutive ids
+            // go to LDS (a wave per group, lanes = ids); wave 0 then finds the group that holds u_emit * total (every
+            // lane sums a run of groups, a scan over the lanes, then that lane's groups in order) and the id inside it.
+            if (vec) {
+                // a wave takes 256 ids = four groups at a time, a lane four consecutive ids, 16 lanes a group
+#pragma unroll 2
+                for (int sg = wave; sg * 256 < vocab; sg += 16) {
+                    const int i = sg * 64 + lane;
+                    float x = 0.f;
+                    if (4 * i < vocab) {
+                        const float4 r = current4(i);
+                        x = (r.x + r.y) + (r.z + r.w);
+                    }
+                    for (int o = 8; o > 0; o >>= 1) x += __shfl_xor(x, o);
+                    const int g = sg * 4 + (lane >> 4);
+                    if ((lane & 15) == 0 && g < n_groups) s_grp[g] = x;
+                }
+            } else {
+                for (int g = wave; g < n_groups; g += 16) {
+                    const int v = g * 64 + lane;
+                    float r = v < vocab ? current(v) : 0.f;
+                    for (int o = 32; o > 0; o >>= 1) r += __shfl_xor(r, o);
+                    if (lane == 0) s_grp[g] = r;
+                }
             }
             __syncthreads();
-            if (action == 1) continue;
-            if (t == 0) {
-                const float target = u_emit[b] * s_total;
-                float cum = 0.f;
-                int seg = 1023;
-                for (int i = 0; i < 1024; ++i) {
-                    if (target < cum + s_part[i]) { seg = i; break; }
-                    cum += s_part[i];
+            if (wave == 0) {
+                const int gpl = (n_groups + 63) >> 6;                        // groups per lane
+                float ls = 0.f;
+                for (int i = 0; i < gpl; ++i) {
+                    const int g = lane * gpl + i;
+                    ls += g < n_groups ? s_grp[g] : 0.f;
                 }
-                const int w0 = seg * per, w1 = min(vocab, w0 + per);
-                int pick = -1, last_nonzero = -1;
-                for (int v = w0; v < w1; ++v) {
-                    const float w = current(v);
-                    if (w > 0.f) last_nonzero = v;
-                    if (target < cum + w) { pick = v; break; }
-                    cum += w;
+                float inc = ls;                                              // inclusive scan over the lanes
+                for (int o = 1; o < 64; o <<= 1) {
+                    const float y = __shfl_up(inc, o);
+                    if (lane >= o) inc += y;
                 }
-                if (pick < 0) pick = last_nonzero >= 0 ? last_nonzero : min(w0, vocab - 1);   // rounding at the very end of the range
-                s_pick = pick;
+                const float target = u_emit[b] * __shfl(inc, 63);
+                const unsigned long long hit = __ballot(target < inc);
+                const int L = hit ? __ffsll((long long)hit) - 1 : 63;
+                float cum = __shfl(inc - ls, L);                             // weight before lane L's groups
+                int gsel = min((L + 1) * gpl, n_groups) - 1;
+                for (int i = 0; i < gpl; ++i) {                              // uniform: every lane walks lane L's groups
+                    const int g = L * gpl + i;
+                    if (g >= n_groups) break;
+                    const float gs = s_grp[g];
+                    if (target < cum + gs) { gsel = g; break; }
+                    cum += gs;
+                }
+                const int v = gsel * 64 + lane;
+                const float w = v < vocab ? current(v) : 0.f;
+                float winc = w;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const float y = __shfl_up(winc, o);
+                    if (lane >= o) winc += y;
+                }
+                const unsigned long long first = __ballot(target < cum + winc && w > 0.f), any = __ballot(w > 0.f);
+                int pick;
+                if (first) pick = gsel * 64 + __ffsll((long long)first) - 1;
+                else if (any) pick = gsel * 64 + 63 - __clzll((long long)any);       // rounding at the very end: the last id with weight
+                else pick = min(gsel * 64, vocab - 1);
+                if (lane == 0) s_pick = pick;
             }
             __syncthreads();
             tok = s_pick;
             break;
         }
     }
+    __syncthreads();
+    if (t < SEV_MAX_DRAFT) pend_path[(size_t)slot * SEV_MAX_DRAFT + t] = t < s.a ? s.path[t] : -1;
+    if (path_out && t < k_max) path_out[(size_t)b * k_max + t] = t < s.a ? s.path[t] : -1;
     if (t == 0) {
         const int a = s.a;
-        int32_t *path = pend_path + (size_t)slot * SEV_MAX_DRAFT;
-        for (int i = 0; i < SEV_MAX_DRAFT; ++i) path[i] = i < a ? s.path[i] : -1;
         pend_n[slot] = n;
         pend_a[slot] = a;
         pend_bonus[slot] = tok;
         accept_len[b] = a;
         emitted[b] = tok;
-        if (path_out)
-            for (int i = 0; i < k_max; ++i) path_out[(size_t)b * k_max + i] = i < a ? s.path[i] : -1;
     }
 }
 
@@ -472,7 +569,7 @@ void launch_sample(const sev_kv *kv, int B, int k_max, int rows, const int32_t *
     const int vocab = kv->model->d.vocab;
     const float inv_t = 1.0f / temperature;
     hipLaunchKernelGGL(softmax_stats_kernel, dim3(rows), dim3(1024), 0, st, logits, vocab, inv_t, stats);
-    hipLaunchKernelGGL(sample_walk_kernel, dim3(B), dim3(1024), 0, st, kv->plan, k_max, tokens, parents, logits, draft_probs, stats, vocab,
+    hipLaunchKernelGGL(sample_walk_kernel, dim3(B), dim3(1024), (size_t)((vocab + 63) / 64) * 4, st, kv->plan, k_max, tokens, parents, logits, draft_probs, stats, vocab,
                        inv_t, u_acc, u_emit, kv->next_tok, kv->err_flags, kv->pend_n, kv->pend_a, kv->pend_bonus, kv->pend_path, accept_len,
                        emitted, accept_path);
 }
