@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--padded-kv", action="store_true",
                     help="comparison run, not the headline: attention walks the longest request's length for every request "
                          "(the paper's padded KV + dense mask); reported under its own metric name")
+    ap.add_argument("--stochastic", action="store_true",
+                    help="comparison run, not the headline: the accept / resample rule at temperature 0.7 (sev_verify_sample) with "
+                         "synthetic edge distributions; reported under its own metric name")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device copies (a kernel of known HBM traffic, for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -82,8 +85,21 @@ def main():
     acc = torch.empty(B, dtype=torch.int32, device="cuda")
     bon = torch.empty(B, dtype=torch.int32, device="cuda")
 
+    if args.stochastic:
+        # edge distributions: a softmax of seeded normal scores (scale 3: a few likely ids per row, like a small draft
+        # model's output), the drafts drawn greedily from them except node 0 (the server's previous token)
+        gen = torch.Generator(device="cuda").manual_seed(wl.seed)
+        q_dev = torch.softmax(3.0 * torch.randn(B * k, shape.vocab, device="cuda", generator=gen), dim=-1).contiguous()
+        u_acc = torch.rand(B, k, device="cuda", generator=gen)
+        u_emit = torch.rand(B, device="cuda", generator=gen)
+        batch.kv.set_state(None, lens, nt0)                                # rewind the greedy continuation above
+        s_out = sev.verify_sample(model, batch.kv, lens, d_dev, k, q_dev, u_acc, u_emit, 0.7)
+        acc = s_out["accept_len"]
+
     def step():
-        if args.padded_kv:
+        if args.stochastic:
+            sev.verify_sample(model, batch.kv, lens, d_dev, k, q_dev, u_acc, u_emit, 0.7, out=s_out)
+        elif args.padded_kv:
             sev.verify_ex(model, batch.kv, lens, d_dev, k, mode=2, accept_len=acc, bonus_token=bon)
         else:
             sev.verify(model, batch.kv, lens, d_dev, None, B, k, acc, bon)
@@ -149,8 +165,9 @@ def main():
     # (KiB per dispatch x the factor a plain 1 GiB copy gives each counter); they hold for this one launch shape
     traffic = (123017.5 * 2.0 + 7168.0 * 1.0) * 1024.0 if (wl.name == "8b-chain-b16k8" and not os.environ.get("SEV_TUNE_GU")) else None
     out = {
-        "metric": ("verified draft tokens/sec on 1 MI355X (8B-shape bf16, B=16, k=8); % roofline" if not args.padded_kv else
-                   "COMPARISON RUN (padded KV + dense mask): verified draft tokens/sec on 1 MI355X"),
+        "metric": ("COMPARISON RUN (accept / resample rule at temperature 0.7): verified draft tokens/sec on 1 MI355X" if args.stochastic else
+                   "COMPARISON RUN (padded KV + dense mask): verified draft tokens/sec on 1 MI355X" if args.padded_kv else
+                   "verified draft tokens/sec on 1 MI355X (8B-shape bf16, B=16, k=8); % roofline"),
         "value": tokens / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "emitted_tokens_per_s": float((accept + 1).sum()) / (ms_per_step * 1e-3),
@@ -159,7 +176,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "model_shape": shape.name, "B": B, "k": k, "rows_per_step": tokens,
                    "sum_prefix_tokens": int(sum(lens)), "page_size": 16,
-                   "padded_kv": bool(args.padded_kv), "mean_accept_len": float(accept.mean()), "precision": "bf16 weights/KV, split-bf16 activations, f32 accumulate"},
+                   "padded_kv": bool(args.padded_kv), "stochastic": bool(args.stochastic), "mean_accept_len": float(accept.mean()), "precision": "bf16 weights/KV, split-bf16 activations, f32 accumulate"},
         "roofline": {"bound": "hbm", "kernel": "gemm_gate_up_swiglu", "achieved": achieved, "peak": 8000.0, "unit": "GB/s",
                      "frac": achieved / 8000.0, "traffic": traffic, "bytes_per_launch": gu_bytes,
                      "avg_launch_ms": gu_avg_ms, "launches_timed": gu_n, "empty_event_pair_ms": empty_ms,

@@ -265,13 +265,15 @@ def verify_ex(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor
 
 def verify_sample(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor, k_max: int, draft_probs: torch.Tensor,
                   u_accept: torch.Tensor, u_emit: torch.Tensor, temperature: float, slots=None, draft_lens=None,
-                  parents: torch.Tensor = None):
-    """sev_verify_sample: returns a dict of device tensors (accept_len, emitted_token, accept_path, logits)."""
+                  parents: torch.Tensor = None, out: dict = None):
+    """sev_verify_sample: returns a dict of device tensors (accept_len, emitted_token, accept_path, logits); a dict
+    returned by an earlier call of the same shape can be passed back as `out` to reuse its tensors."""
     pl, sl, dl = _host_i32(prefix_lens), _host_i32(slots), _host_i32(draft_lens)
     B = len(pl)
     rows = int(dl.sum()) if dl is not None else B * k_max
     dev = model.device
-    out = {"accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+    out = out if out is not None else {
+           "accept_len": torch.empty(B, dtype=torch.int32, device=dev),
            "emitted_token": torch.empty(B, dtype=torch.int32, device=dev),
            "accept_path": torch.empty(B, k_max, dtype=torch.int32, device=dev),
            "logits": torch.empty(rows, model.desc.vocab, dtype=torch.float32, device=dev)}
