@@ -39,3 +39,12 @@ def test_host_side_validation_without_gpu():
     h = ctypes.c_void_p()
     assert L.sev_model_create(ctypes.byref(ok), None, 0, ctypes.byref(h)) == -1
     assert L.sev_verify(None, None, None, None, None, 1, 1, None, None, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: any other --gpus value ends with a message and a non-zero status before torch is imported."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
