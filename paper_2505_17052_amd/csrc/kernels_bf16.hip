@@ -447,7 +447,8 @@ template <int MT, int NT, int EPI, int PF>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const uint4 *X_, int n_tiles_, int k_steps_, int m_tiles_total_,
                                                         int col_groups_, int m_blocks_, int splits_, GemmArgs g) {
     g.W = W_; g.X = X_; g.n_tiles = n_tiles_; g.k_steps = k_steps_; g.m_tiles_total = m_tiles_total_;
-    g.col_groups = col_groups_; g.m_blocks = m_blocks_; g.splits = splits_;
+    g.col_groups = col_groups_; g.m_blocks = m_blocks_; g.splits = splits_ & 0xffff;
+    const int tpb = splits_ >> 16;                      // column tiles per block: 4 * NT, or fewer (the last wave then has fewer tiles)
     // a pipeline stage is KS k-steps of 16: two for the narrow tiles, one for NT = 4 (same 32 MFMAs per wave with MT = 4)
     constexpr int KS = NT == 4 ? 1 : 2;
     constexpr int XI = KS * MT / 2;                     // 16-byte activation loads per thread and stage
@@ -466,7 +467,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     const int split = q % g.splits;
     const int cg = (q / g.splits) * 8 + (blockIdx.x & 7);
     if (cg >= g.col_groups) return;                      // whole block leaves before any barrier
-    const int tile0 = (cg * 4 + wave) * NT;
+    const int tile0 = cg * tpb + wave * NT;
+    const int my_tiles = min(NT, min(tpb - wave * NT, g.n_tiles - tile0));        // may be <= 0: the wave then only helps with the activations
     const int mt0 = mb * MT;
     const int n_stages = g.k_steps / KS;
     const int s_begin = (int)((unsigned)n_stages * (unsigned)split / (unsigned)g.splits);          // small numbers: 32-bit division
@@ -489,6 +491,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
         const int t = min(tile0 + a, g.n_tiles - 1);
         wp[a] = (const u32x4 *)g.W + ((size_t)t * g.k_steps) * 64 + lane;
     }
+    // The gate/up GEMM reads its weights through a buffer descriptor that covers exactly the block's column tiles: a
+    // tile the wave does not have (blocks of fewer than 4 * NT tiles, the matrix edge) lies past the descriptor's
+    // end, where a load returns zeros and reads nothing, so the loop stays free of branches and the missing tile
+    // costs no memory traffic.
+    constexpr bool WBUF = EPI == EPI_SWIGLU;
+    const int block_tiles = min(tpb, g.n_tiles - cg * tpb);
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)((const u32x4 *)g.W + (size_t)cg * tpb * g.k_steps * 64), 0, block_tiles * g.k_steps * 1024, 0x00020000);
+    int woff[NT];
+#pragma unroll
+    for (int a = 0; a < NT; ++a) woff[a] = (((wave * NT + a) * g.k_steps) * 64 + lane) * 16;
+    auto load_w = [&](int a, int step) -> u32x4 {      // 16 bytes per lane of k-step `step` of the wave's column tile a
+        // The streaming hint keeps the weights from displacing the activations in the L2s (gate/up: 7 % faster with it).
+        // The QKV projection streams the fewest weights per activation byte and is 4 % faster with plain loads.
+        if constexpr (WBUF) return __builtin_amdgcn_raw_buffer_load_b128(wrs, woff[a] + step * 1024, 0, 2);      // 2: streaming hint
+        else if constexpr (EPI == EPI_QKV) return wp[a][(size_t)step * 64];
+        else return __builtin_nontemporal_load(&wp[a][(size_t)step * 64]);
+    };
     // Software pipeline.  Loads return in issue order, so a wait on one load drains every older one:
     // to keep PF stages in flight, weights AND activations are fetched PF stages ahead into registers
     // and consumed in the order they were issued.  At the start of stage st (slot u = st % PF):
@@ -543,7 +563,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
 #pragma unroll
             for (int a = 0; a < NT; ++a)
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
+                for (int ks = 0; ks < KS; ++ks) wreg[u][a][ks] = load_w(a, KS * sw + ks);
         }
 #pragma unroll
         for (int i = 0; i < XI; ++i) {
@@ -607,7 +627,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
                             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, as_bf16x8(xf[ks][b][pl]), acc[a][b], 0, 0, 0);
                             if (a == NT - 1) xf[ks][b][pl] = xnext[((ks * MT + b) * 2 + pl) * 64];
                         }
-                    if constexpr (LOAD) wreg[u][a][ks] = __builtin_nontemporal_load(&wp[a][(size_t)(KS * sw + ks) * 64]);
+                    if constexpr (LOAD) wreg[u][a][ks] = load_w(a, KS * sw + ks);
                     if (ks == 0 && a == 0) {
 #pragma unroll
                         for (int i = 0; i < XI; ++i) xd[256 * i] = live ? xreg[u][i] : zero4;
@@ -675,7 +695,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
             const float rs_b = g.ssq_in ? rms_scale(sq_rows[b], g.inv_d, g.eps) : 1.0f;
 #pragma unroll
             for (int a = 0; a < NT; ++a)
-                if (tile0 + a < g.n_tiles) {
+                if (a < my_tiles) {
                     const TilePre pre = tile_pre<EPI, true>(g, tile0 + a, m, nsub, rs_b);
                     ss[b] += tile_epilogue<EPI>(g, acc[a][b], tile0 + a, m, nsub, pre);
                 }
@@ -699,7 +719,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
             int bi = 0x7fffffff;
 #pragma unroll
             for (int a = 0; a < NT; ++a) {
-                if (tile0 + a >= g.n_tiles) continue;
+                if (a >= my_tiles) continue;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int nn = (tile0 + a) * 32 + 8 * j + nsub;
@@ -1153,6 +1173,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const int4 *mg_rec, con
 // ---------------------------------------------------------------------------
 struct GemmCfg {
     int MT, NT, S, PF;
+    int T;                  // column tiles per block (4 * NT unless a narrower block fills the chip better)
 };
 
 enum { G_QKV = 0, G_O, G_GU, G_DOWN, G_LM };
@@ -1201,6 +1222,21 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
         }
     }
     c.S = std::min(c.S, std::max(1, k_steps / 2));
+    // The unsplit gate/up GEMM, when it leaves compute units idle: blocks one or two column tiles narrower (the last
+    // wave of a block then has fewer tiles than the others) if that brings the block count closer to the number of
+    // compute units.  With few rows the kernel is bound by the requests a compute unit can keep in flight, so every
+    // unit counts: the 8B shape has 896 column tiles, 112 x 2 = 224 blocks of 8 or 128 x 2 = 256 blocks of 7.
+    c.T = 4 * c.NT;
+    if (c.S == 1 && which == G_GU && c.MT <= 2) {
+        const int m_blocks = (m_tiles + c.MT - 1) / c.MT;
+        auto blocks_t = [&](int t) { return ((n_tiles + t - 1) / t) * m_blocks; };
+        for (int t = 4 * c.NT - 1; t >= 3 * c.NT + 1; --t)
+            if (blocks_t(4 * c.NT) < 256 && blocks_t(t) <= 256 && blocks_t(t) > blocks_t(c.T)) c.T = t;
+    }
+    if (const char *e = getenv("SEV_TUNE_TPB")) {        // tuning experiments: tiles per block of the gate/up GEMM
+        const int t = atoi(e);
+        if (which == G_GU && c.S == 1 && t >= 3 * c.NT + 1 && t <= 4 * c.NT) c.T = t;
+    }
     // the exchange buffer holds S slices of (padded columns) x (padded rows)
     const size_t slice = (size_t)blocks_of(c) * 4 * c.NT * c.MT * 1024;
     while (c.S > 1 && (size_t)c.S * slice > part_elems) --c.S;
@@ -1209,7 +1245,7 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
 
 template <int EPI>
 static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t st) {
-    ga.col_groups = (ga.n_tiles + 4 * c.NT - 1) / (4 * c.NT);
+    ga.col_groups = (ga.n_tiles + c.T - 1) / c.T;
     ga.m_blocks = (m_tiles + c.MT - 1) / c.MT;
     ga.splits = c.S;
     ga.mt = c.MT;
@@ -1219,7 +1255,7 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     const size_t lds = (size_t)2 * (c.NT == 4 ? 1 : 2) * c.MT * 2 * 64 * 16;
 #define SEV_LAUNCH(MT_, NT_, PF_)                                                                                     \
     hipLaunchKernelGGL((gemm_bf16_kernel<MT_, NT_, EPI, PF_>), grid, dim3(256), lds, st, ga.W, ga.X, ga.n_tiles, ga.k_steps,         \
-                       ga.m_tiles_total, ga.col_groups, ga.m_blocks, ga.splits, ga)
+                       ga.m_tiles_total, ga.col_groups, ga.m_blocks, ga.splits | (c.T << 16), ga)
 #define SEV_BY_NT(MT_, PF_)                                                                                           \
     do {                                                                                                              \
         if (c.NT == 2) SEV_LAUNCH(MT_, 2, PF_); else SEV_LAUNCH(MT_, 1, PF_);                                         \
