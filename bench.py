@@ -163,7 +163,7 @@ def main():
     tokens = B * k
     # HBM bytes per gate/up launch from the rocprofv3 FETCH_SIZE and WRITE_SIZE runs kept under profiles/
     # (KiB per dispatch x the factor a plain 1 GiB copy gives each counter); they hold for this one launch shape
-    traffic = (123017.5 * 2.0 + 7168.0 * 1.0) * 1024.0 if (wl.name == "8b-chain-b16k8" and not os.environ.get("SEV_TUNE_GU")) else None
+    traffic = (123035.7 * 2.0 + 7168.0 * 1.0) * 1024.0 if (wl.name == "8b-chain-b16k8" and not os.environ.get("SEV_TUNE_GU")) else None
     out = {
         "metric": ("COMPARISON RUN (accept / resample rule at temperature 0.7): verified draft tokens/sec on 1 MI355X" if args.stochastic else
                    "COMPARISON RUN (padded KV + dense mask): verified draft tokens/sec on 1 MI355X" if args.padded_kv else
