@@ -747,166 +747,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     SEV_TRACE_END(1);
 }
 
-// ---------------------------------------------------------------------------
-// Gate/up GEMM for few rows, operand roles swapped: a block computes 128 rows x 128 columns, wave w owns row
-// tile w and all four column tiles.  The weights of the block's four column tiles go through LDS (each byte of
-// the weight matrix enters exactly one compute unit), the wave's own activation fragments (two planes) come
-// straight from global memory into registers.  Same MFMA operand order as gemm_bf16_kernel (A = weights,
-// B = activations), so the accumulator layout and the epilogue are the same.
-// Why: a compute unit's load path is what bounds the GEMMs at 128 rows, and weight misses are what it pays for;
-// with 64-row blocks every weight byte is requested by two units (the second request waits for the same fill),
-// with 128-row blocks by one.  The fragment traffic from LDS stays at 0.5 KiB per MFMA.
-// Pipeline as in gemm_bf16_kernel: stage = 2 k-steps, PF stages of loads in flight, LDS double buffer.
-// ---------------------------------------------------------------------------
-template <int PF>
-__global__ __launch_bounds__(256) void gemm_gu_rows_kernel(const uint4 *W_, const uint4 *X_, int n_tiles_, int k_steps_, int m_tiles_total_,
-                                                           int col_groups_, int m_blocks_, GemmArgs g) {
-    g.W = W_; g.X = X_; g.n_tiles = n_tiles_; g.k_steps = k_steps_; g.m_tiles_total = m_tiles_total_;
-    g.col_groups = col_groups_; g.m_blocks = m_blocks_;
-    constexpr int KS = 2, CT = 4;                       // k-steps per stage, column tiles per block
-    constexpr int WI = KS * CT / 4;                     // 16-byte weight loads per thread and stage (= 2)
-    constexpr int STAGE_U4 = KS * CT * 64;
-    extern __shared__ u32x4 ws[];                       // [2 buffers][KS][CT][64 lanes]
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int q = blockIdx.x >> 3;
-    const int mb = q % g.m_blocks;
-    q /= g.m_blocks;
-    const int cg = q * 8 + (blockIdx.x & 7);
-    if (cg >= g.col_groups) return;
-    const int tile0 = cg * CT;
-    const int rt = mb * 4 + wave;                       // this wave's row tile
-    const int n = g.k_steps / KS;
-    const int mrow = lane & 31, nsub = 4 * (lane >> 5);
-
-    f32x16 acc[CT];
-#pragma unroll
-    for (int f = 0; f < CT; ++f)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[f][r] = 0.f;
-
-    // this thread's share of a weight stage: unit u = ks * 256 + tile * 64 + lane  (u = threadIdx.x + 256 i)
-    const u32x4 *wsrc[WI];
-#pragma unroll
-    for (int i = 0; i < WI; ++i) {
-        const int u = threadIdx.x + 256 * i;
-        const int ks = u >> 8, t = min(tile0 + ((u >> 6) & 3), g.n_tiles - 1);
-        wsrc[i] = (const u32x4 *)g.W + ((size_t)t * g.k_steps + ks) * 64 + (u & 63);
-    }
-    // the wave's activation fragments: [k-step][row tile][plane][lane]
-    const u32x4 *xp = (const u32x4 *)g.X + (size_t)min(rt, g.m_tiles_total - 1) * 128 + lane;
-    const size_t x_kstep = (size_t)g.m_tiles_total * 128;
-    const int n_pad = (n + PF - 1) / PF * PF;
-    const int rot = n >= 64 ? (int)((unsigned)cg * (unsigned)n / (unsigned)g.col_groups) : 0;
-    auto phys = [&](int t) {
-        int i = min(t, n - 1) + rot;
-        if (i >= n) i -= n;
-        return i;
-    };
-    static_assert(PF % 2 == 0, "LDS buffer parity must follow the slot index");
-    // (Stages beyond the slice are never multiplied: the groups that load cover real stages only, and the last
-    // group stops at the slice's end.  Loads that point beyond it re-read the last stage.)
-    u32x4 xreg[PF][KS][2];                              // X(st): the wave's fragments, straight from memory
-    u32x4 wreg[PF][WI];                                 // W(st + 2) on its way to LDS
-    u32x4 wf[KS][CT];                                   // W(st) fragments
-    {
-        u32x4 w0[WI], w1[WI];
-#pragma unroll
-        for (int i = 0; i < WI; ++i) {
-            w0[i] = __builtin_nontemporal_load(&wsrc[i][(size_t)phys(0) * KS * 64]);
-            w1[i] = __builtin_nontemporal_load(&wsrc[i][(size_t)phys(1) * KS * 64]);
-        }
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int sx = phys(u), sw = phys(u + 2);
-#pragma unroll
-            for (int i = 0; i < WI; ++i) wreg[u][i] = __builtin_nontemporal_load(&wsrc[i][(size_t)sw * KS * 64]);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl) xreg[u][ks][pl] = xp[(size_t)(KS * sx + ks) * x_kstep + pl * 64];
-        }
-#pragma unroll
-        for (int i = 0; i < WI; ++i) {
-            ws[threadIdx.x + 256 * i] = w0[i];
-            ws[STAGE_U4 + threadIdx.x + 256 * i] = w1[i];
-        }
-    }
-    const int m = rt * 32 + mrow;
-    const unsigned long long sq_row = (g.ssq_in && m < g.M) ? g.ssq_in[m] : 0ull;
-    SEV_ARGS_NOW("s"(g.ssq_in), "s"(g.act));
-    __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int f = 0; f < CT; ++f) wf[ks][f] = ws[(ks * CT + f) * 64 + lane];
-    __syncthreads();                                    // stage 0 overwrites buffer 0 early
-
-    auto group = [&](int base, auto load_tag) {
-        constexpr bool LOAD = decltype(load_tag)::value;
-#pragma unroll
-        for (int u = 0; u < PF; ++u) {
-            const int st = base + u;
-            if constexpr (!LOAD) {
-                if (st >= n) break;
-            }
-            const u32x4 *wnext = ws + ((u + 1) & 1) * STAGE_U4 + lane;       // W(st+1)
-            u32x4 *wd = ws + (u & 1) * STAGE_U4 + threadIdx.x;
-            const int sx = phys(st + PF), sw = phys(st + PF + 2);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl) {
-                    const bf16x8 x = as_bf16x8(xreg[u][ks][pl]);
-#pragma unroll
-                    for (int f = 0; f < CT; ++f) {
-                        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(wf[ks][f]), x, acc[f], 0, 0, 0);
-                        if (pl == 1) wf[ks][f] = wnext[(ks * CT + f) * 64];
-                    }
-                    if constexpr (LOAD) xreg[u][ks][pl] = xp[(size_t)(KS * sx + ks) * x_kstep + pl * 64];
-                    if (ks == 0 && pl == 0) {
-#pragma unroll
-                        for (int i = 0; i < WI; ++i) wd[256 * i] = wreg[u][i];
-                        if constexpr (LOAD) {
-#pragma unroll
-                            for (int i = 0; i < WI; ++i) wreg[u][i] = __builtin_nontemporal_load(&wsrc[i][(size_t)sw * KS * 64]);
-                        }
-                    }
-                }
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl) {
-                    if (pl == 0) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, CT, 0);
-                    } else {
-#pragma unroll
-                        for (int f = 0; f < CT; ++f) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        }
-                    }
-                    if constexpr (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                    if (ks == 0 && pl == 0) {
-                        __builtin_amdgcn_sched_group_barrier(0x200, WI, 0);
-                        if constexpr (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, WI, 0);
-                    }
-                }
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-        }
-    };
-    for (int base = 0; base + PF < n_pad; base += PF) group(base, std::true_type{});
-    group(n_pad - PF, std::false_type{});
-
-    const float rs = g.ssq_in ? rms_scale(sq_row, g.inv_d, g.eps) : 1.0f;
-#pragma unroll
-    for (int f = 0; f < CT; ++f)
-        if (tile0 + f < g.n_tiles && rt < g.m_tiles_total) {
-            const TilePre pre = tile_pre<EPI_SWIGLU, true>(g, tile0 + f, m, nsub, rs);
-            tile_epilogue<EPI_SWIGLU>(g, acc[f], tile0 + f, m, nsub, pre);
-        }
-}
-
 // Split-K fix-up: block (column group cg, row tile mt, a) of 4 waves; wave w sums the S slices of the
 // 32x32 tile (column tile (cg*4 + w)*NT + a, row tile mt) in slice order and runs its epilogue.
 template <int EPI>
@@ -1457,8 +1297,6 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
     const GemmCfg pg = choose_cfg(G_GU, m_tiles_real, d.d_ffn / 16, d.d_model / 16, kv->part_elems);
     const GemmCfg pd = choose_cfg(G_DOWN, m_tiles_real, d.d_model / 32, d.d_ffn / 16, kv->part_elems);
     const GemmCfg pl = choose_cfg(G_LM, m_tiles_real, d.vocab / 32, d.d_model / 16, kv->part_elems);
-    bool gu_rows = m_tiles_real <= 4 && (d.d_model / 16) % 2 == 0;
-    if (const char *e = getenv("SEV_TUNE_GUROWS")) gu_rows = gu_rows && atoi(e) != 0;      // tuning experiments: 0 = the column-split kernel
     GemmArgs base;
     memset(&base, 0, sizeof(base));
     base.m_tiles_total = m_tiles;
@@ -1504,15 +1342,7 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             GemmArgs ga = base;
             ga.W = Wp(lo.wgu); ga.X = (const uint4 *)xa; ga.n_tiles = d.d_ffn / 16; ga.k_steps = d.d_model / 16;
             ga.N = 2 * d.d_ffn; ga.act = act; ga.ssq_in = kv->ssq[0];
-            if (gu_rows) {                               // up to 128 rows: 128 x 128 blocks, every weight byte into one compute unit
-                ga.col_groups = (ga.n_tiles + 3) / 4;
-                ga.m_blocks = (m_tiles_real + 3) / 4;
-                ga.splits = 1; ga.mt = 1; ga.nt = 4;
-                const unsigned blocks = (unsigned)((ga.col_groups + 7) / 8 * 8 * ga.m_blocks);
-                hipLaunchKernelGGL((gemm_gu_rows_kernel<4>), dim3(blocks), dim3(256), (size_t)2 * 2 * 4 * 64 * 16, st, ga.W, ga.X, ga.n_tiles,
-                                   ga.k_steps, ga.m_tiles_total, ga.col_groups, ga.m_blocks, ga);      // (6 or 8 stages in flight: no faster)
-            } else
-                launch_gemm<EPI_SWIGLU>(ga, pg, m_tiles_real, st);
+            launch_gemm<EPI_SWIGLU>(ga, pg, m_tiles_real, st);
         }
         {   // down projection; residual add, next norm's operand and scale in its epilogue
             Prof p(kv, st, PROF_GEMM_DOWN);
