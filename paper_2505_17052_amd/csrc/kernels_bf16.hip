@@ -495,7 +495,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     // tile the wave does not have (blocks of fewer than 4 * NT tiles, the matrix edge) lies past the descriptor's
     // end, where a load returns zeros and reads nothing, so the loop stays free of branches and the missing tile
     // costs no memory traffic.
-    constexpr bool WBUF = EPI == EPI_SWIGLU;
+    constexpr bool WBUF = EPI == EPI_SWIGLU && MT <= 2;      // the 128-row blocks never run narrower than 4 * NT tiles
     const int block_tiles = min(tpb, g.n_tiles - cg * tpb);
     const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
         (void *)((const u32x4 *)g.W + (size_t)cg * tpb * g.k_steps * 64), 0, block_tiles * g.k_steps * 1024, 0x00020000);
