@@ -59,7 +59,9 @@ class Model:
 
     tensor(name, layer) returns a float array in canonical [out_features,
     in_features] layout for name in {embed, lm_head, wq, wk, wv, wo, wg, wu, wd}
-    (layer is ignored for embed / lm_head).  Norm gains are 1.
+    (layer is ignored for embed / lm_head).  gains(name, layer), if given, returns
+    the RMSNorm gain vector [d_model] for name in {norm_attn, norm_ffn, norm_final}
+    (layer ignored for norm_final); without it every gain is 1.
     """
     n_layers: int
     d_model: int
@@ -74,6 +76,7 @@ class Model:
     dtype: type = np.float64
     cache_weights: bool = True
     kv_bf16: bool = False            # the KV cache stores bfloat16 (round-to-nearest-even on write)
+    gains: Optional[Callable[[str, int], np.ndarray]] = None
     _memo: dict = field(default_factory=dict, repr=False)
 
     def w(self, name: str, layer: int = 0) -> np.ndarray:
@@ -84,6 +87,12 @@ class Model:
         if self.cache_weights:
             self._memo[key] = t
         return t
+
+    def g(self, name: str, layer: int = 0):
+        """RMSNorm gain vector (1.0 when the model has unit gains)."""
+        if self.gains is None:
+            return 1.0
+        return np.asarray(self.gains(name, layer)).astype(self.dtype, copy=False)
 
 
 class Cache:
@@ -255,7 +264,7 @@ def forward_blocks(model: Model, caches: Sequence[Cache], tokens: Sequence[np.nd
     new_v = [[None] * m.n_layers for _ in range(R)]
     M = len(all_tok)
     for l in range(m.n_layers):
-        x = rmsnorm(h, 1.0, m.rms_eps)
+        x = rmsnorm(h, m.g("norm_attn", l), m.rms_eps)
         q = (x @ m.w("wq", l).T).reshape(M, m.n_q_heads, m.head_dim)
         k = (x @ m.w("wk", l).T).reshape(M, m.n_kv_heads, m.head_dim)
         v = (x @ m.w("wv", l).T).reshape(M, m.n_kv_heads, m.head_dim)
@@ -273,12 +282,12 @@ def forward_blocks(model: Model, caches: Sequence[Cache], tokens: Sequence[np.nd
             new_k[r][l] = k[a:b].copy()
             new_v[r][l] = v[a:b].copy()
         h = h + o.reshape(M, -1) @ m.w("wo", l).T
-        x = rmsnorm(h, 1.0, m.rms_eps)
+        x = rmsnorm(h, m.g("norm_ffn", l), m.rms_eps)
         act = silu(x @ m.w("wg", l).T) * (x @ m.w("wu", l).T)
         h = h + act @ m.w("wd", l).T
     logits = None
     if want_logits:
-        full = rmsnorm(h, 1.0, m.rms_eps) @ m.w("lm_head").T
+        full = rmsnorm(h, m.g("norm_final"), m.rms_eps) @ m.w("lm_head").T
         logits = [full[offs[r]:offs[r + 1]] for r in range(R)]
     return logits, new_k, new_v
 

@@ -14,9 +14,10 @@ def _to_device(arr: np.ndarray, device) -> torch.Tensor:
     return torch.from_numpy(arr).to(device)
 
 
-def build_model(shape: synth.ModelShape, seed: int, device="cuda:0", progress=None) -> sev.Model:
+def build_model(shape: synth.ModelShape, seed: int, device="cuda:0", progress=None, gains=False) -> sev.Model:
     """Creates a model and loads every matrix from the seeded weight source, one tensor at a time
-    (host generation -> staging tensor -> sev_model_load_tensor), so peak staging is one tensor."""
+    (host generation -> staging tensor -> sev_model_load_tensor), so peak staging is one tensor.
+    gains=True also loads the source's seeded non-unit norm gains (the default gains are 1)."""
     dt = sev.SEV_F32 if shape.dtype == "f32" else sev.SEV_BF16
     m = sev.Model(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
                   shape.vocab, shape.rope_base, shape.rms_eps, dt, device)
@@ -26,8 +27,13 @@ def build_model(shape: synth.ModelShape, seed: int, device="cuda:0", progress=No
     for l in range(shape.n_layers):
         for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
             m.load_tensor(name, l, _to_device(src.tensor(name, l), m.device))
+        if gains:
+            for name in ("norm_attn", "norm_ffn"):
+                m.load_tensor(name, l, _to_device(src.gain(name, l), m.device))
         if progress:
             progress(l)
+    if gains:
+        m.load_tensor("norm_final", 0, _to_device(src.gain("norm_final"), m.device))
     torch.cuda.synchronize()
     return m
 

@@ -79,7 +79,8 @@ class WeightSource:
 
     For "bf16" shapes the values are bfloat16 (round-to-nearest-even of the normal
     draw) and are returned as uint16 bit patterns; for "f32" shapes as float32.
-    Norm gains are exactly 1 and there are no biases, so they are not generated.
+    The workloads use unit norm gains and no biases; `gain` draws non-unit gains for
+    the tests that check that the gains are applied.
     """
 
     def __init__(self, shape: ModelShape, seed: int):
@@ -106,6 +107,13 @@ class WeightSource:
             flat = rng.normal_f32(self.seed, st, n, self.shape.init_std,
                                   out=None if out is None else out.reshape(-1))
         return flat.reshape(rows, cols)
+
+    def gain(self, name: str, layer: int = 0) -> np.ndarray:
+        """Seeded RMSNorm gain vector [d_model], float32, uniform in [0.5, 1.5);
+        name in {norm_attn, norm_ffn, norm_final} (layer ignored for norm_final)."""
+        kind = {"norm_attn": 9, "norm_ffn": 10, "norm_final": 11}[name]
+        st = stream_id(P_WEIGHT, 0 if name == "norm_final" else layer, kind)
+        return (0.5 + rng.uniform_f64(self.seed, st, self.shape.d_model)).astype(np.float32)
 
     def tensor_f32(self, name: str, layer: int = 0) -> np.ndarray:
         """The tensor's values as float32 (bf16 shapes are widened exactly)."""

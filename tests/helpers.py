@@ -6,12 +6,13 @@ import synth
 from oracle import verify_oracle as vo
 
 
-def oracle_model(shape: synth.ModelShape, seed: int, dtype=np.float64, cache_weights=True) -> vo.Model:
+def oracle_model(shape: synth.ModelShape, seed: int, dtype=np.float64, cache_weights=True, gains=False) -> vo.Model:
+    """gains=True: seeded non-unit RMSNorm gains (synth.WeightSource.gain) instead of ones."""
     src = synth.WeightSource(shape, seed)
     return vo.Model(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                     shape.d_ffn, shape.vocab, shape.rope_base, shape.rms_eps,
                     tensor=src.tensor_f32, dtype=dtype, cache_weights=cache_weights,
-                    kv_bf16=(shape.dtype == "bf16"))
+                    kv_bf16=(shape.dtype == "bf16"), gains=src.gain if gains else None)
 
 
 def corrupt_chain(greedy: np.ndarray, req: synth.workload.Request, n: int) -> np.ndarray:
@@ -28,6 +29,21 @@ def decision_gap_ok(res, gap_min: float) -> bool:
     the last of them also produced the stop decision and the bonus token) has a top-1/top-2 logit gap
     of at least gap_min.  Only such requests are compared bit-exactly."""
     return all(res.top2_gap[i] >= gap_min for i in res.path)
+
+
+def greedy_in_place(om, caches, k: int):
+    """Plain greedy decoding, k single-token forwards from each cache, WITHOUT copying the caches (the large
+    shapes' caches are tens of GB): the decoded tokens' K/V are written behind the committed length, which is put
+    back afterwards, so the caches end as they started.  Same result as vo.greedy_continuation."""
+    state = [(c.length, c.next_tok) for c in caches]
+    out = [[c.next_tok] for c in caches]
+    for _ in range(k):
+        vo.extend(om, caches, [np.array([o[-1]]) for o in out])
+        for r, c in enumerate(caches):
+            out[r].append(c.next_tok)
+    for c, (n, t) in zip(caches, state):
+        c.length, c.next_tok, c.pending = n, t, None
+    return [np.array(o, dtype=np.int64) for o in out]
 
 
 def announce(msg: str):

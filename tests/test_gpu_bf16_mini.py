@@ -95,8 +95,70 @@ def assert_bf16_close(got, ref, what=""):
     tol = np.abs(ref) * 2.0 ** -7 + 5e-5
     bad = int(np.sum(err > tol))
     assert bad == 0, f"{what}: {bad} entries off, worst {float(err.max()):.3e}"
-    # a float32-level difference d flips the rounding of about 2*d*2^8 of the entries: a few per cent by layer 3
+    # A float32-level difference moves some entries across a rounding boundary (they then differ by exactly one
+    # step, which the bound above allows).  How many is derived from the measured difference, layer by layer, in
+    # test_flipped_fraction_follows_the_float32_difference; 0.06 is that prediction for the deepest layer of this
+    # model (about 0.03) times the factor 2 allowed there.
     assert np.mean(got != ref) < 0.06, f"{what}: {np.mean(got != ref):.4f} of entries differ"
+
+
+def predicted_flips(ref, d):
+    """Expected fraction of bf16-rounded entries that change when the unrounded values differ by Gaussian noise of
+    relative rms d (relative to the rms of `ref`): an entry x with bf16 spacing s(x) = 2^(floor(log2 |x|) - 7) flips
+    with probability E|delta| / s(x) = sqrt(2/pi) * d * rms(ref) / s(x) (capped at 1)."""
+    a = np.abs(ref[ref != 0]).astype(np.float64)
+    spacing = 2.0 ** (np.floor(np.log2(a)) - 7)
+    sigma = d * float(np.sqrt(np.mean(ref.astype(np.float64) ** 2)))
+    return float(np.mean(np.minimum(1.0, np.sqrt(2.0 / np.pi) * sigma / spacing)))
+
+
+def test_flipped_fraction_follows_the_float32_difference():
+    """Why some stored K/V entries differ from the oracle's by one rounding step, and how many may.
+
+    Both sides round K/V to bf16.  Before rounding they differ at float32 level (the split-plane GEMMs carry about 16
+    mantissa bits; from layer 1 on the attention has also read entries of earlier layers that were flipped).  The
+    difference d_l of the residual stream that enters layer l is measured here, not assumed: it is the relative rms
+    difference between the GPU's and the oracle's float32 logits of the SAME model truncated to l layers (the logits are
+    a linear map of the normalised stream).  Layer 0 reads the embedding, which is exact on both sides, so its only
+    difference is the GEMM's own: d_0 = 2^-16.  predicted_flips turns d_l into the expected fraction of flipped
+    entries; the observed fraction must stay below twice the prediction (c = 2 covers the Gaussian model of the
+    noise and the rounding of K after the rotary embedding) plus 0.2 % of the entries."""
+    import paper_2505_17052_amd as sev
+    from paper_2505_17052_amd import harness
+    lens, n = [37, 300, 64], 32
+    B = len(lens)
+    last = [int(synth.uniform_i32(SEED, 7000 + b, 1, 0, SHAPE.vocab)[0]) for b in range(B)]
+    block = np.stack([synth.uniform_i32(SEED, 7100 + b, n, 0, SHAPE.vocab) for b in range(B)]).astype(np.int32)
+    d_in = [2.0 ** -16]
+    full = None
+    for L in range(1, SHAPE.n_layers + 1):
+        shp = SHAPE.with_layers(L)
+        model = harness.build_model(shp, SEED)
+        om = oracle_model(shp, SEED, dtype=np.float32)
+        batch = harness.Batch(model, shp, [P + n + 16 for P in lens], max_rows=B * n, seed=SEED)
+        batch.fill_synthetic(SEED, lens, last)
+        caches = oracle_caches_synthetic(om, shp, SEED, lens, last)
+        batch.kv.set_state(None, lens, [c.next_tok for c in caches])
+        out = sev.verify_ex(model, batch.kv, lens, torch.tensor(block, device="cuda"), n, want_logits=True)
+        torch.cuda.synchronize()
+        res = vo.verify(om, caches, [block[b] for b in range(B)])
+        ref = np.concatenate([r.logits for r in res])
+        got = out["logits"].cpu().numpy()
+        d_in.append(float(np.sqrt(np.mean((got - ref) ** 2) / np.mean(ref ** 2))))
+        if L == SHAPE.n_layers:
+            full = (batch, caches)
+    batch, caches = full
+    for l in range(SHAPE.n_layers):
+        obs, pred = [], []
+        for b in range(B):
+            kk, vv = batch.export_kv(b, l, lens[b], n)
+            for got, ref in ((kk, caches[b].pending.new_k[l]), (vv, caches[b].pending.new_v[l])):
+                obs.append(float(np.mean(got != ref)))
+                pred.append(predicted_flips(ref, d_in[l]))
+        o, p = float(np.mean(obs)), float(np.mean(pred))
+        announce(f"  layer {l}: stream difference d = {d_in[l]:.2e}; flipped entries observed {o:.4f}, predicted {p:.4f}")
+        assert o <= 2.0 * p + 0.002, (l, o, p)
+    announce(f"  logit difference of the full model: d = {d_in[-1]:.2e}")
 
 
 def _trim(c):

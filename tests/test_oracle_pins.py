@@ -215,6 +215,72 @@ def test_expected_accept_length_closed_form():
 
 
 # ---------------------------------------------------------------------------
+# arg-max, the top-1/top-2 gap and the tie rule
+# ---------------------------------------------------------------------------
+
+
+def test_argmax_and_gap_hand_cases():
+    """The gap decides which requests are compared bit-exactly; ties go to the lowest id."""
+    lg = np.array([[1.0, 5.0, 3.0, 4.5],        # plain: top 5.0 at id 1, runner-up 4.5
+                   [2.0, 7.0, 7.0, 1.0],        # exact tie of the top two: lowest id, gap 0
+                   [9.0, 3.0, 3.0, -1.0],       # a tie below the top does not matter
+                   [4.0, 4.0, 4.0, 4.0],        # all equal
+                   [-3.0, -0.5, -8.0, -0.75]])  # negative logits
+    am, gap = vo._argmax_and_gap(lg)
+    assert am.tolist() == [1, 1, 0, 0, 1]
+    assert gap.tolist() == [0.5, 0.0, 6.0, 0.0, 0.25]
+    # brute force on random rows, including planted duplicates of the maximum
+    rng = np.random.default_rng(5)
+    rows = rng.integers(-6, 7, size=(200, 9)).astype(np.float64)      # small integers: many exact ties
+    am, gap = vo._argmax_and_gap(rows)
+    for r in range(rows.shape[0]):
+        best = max(rows[r])
+        first = [i for i in range(9) if rows[r][i] == best][0]
+        rest = sorted(rows[r].tolist(), reverse=True)
+        assert am[r] == first and gap[r] == rest[0] - rest[1]
+
+
+def test_tie_rule_through_verify():
+    """A model whose output head has only two non-zero rows, identical and with a single non-zero entry
+    (so that the two dot products are the same number whatever the summation order), at ids a < b: every
+    logit row is (.., s, .., s, ..) with zeros elsewhere.  Where s > 0 the top is tied between a and b; where s < 0 it is
+    tied among all other ids.  The lowest id must win in both cases, and acceptance must follow it."""
+    shape = synth.TINY
+    src = synth.WeightSource(shape, 3)
+    a_id, b_id = 17, 530
+    prompt = synth.rng.uniform_i32(3, 1, 12, 0, shape.vocab)
+    block = synth.rng.uniform_i32(3, 2, 24, 0, shape.vocab)
+    for dim in range(shape.d_model):                     # a hidden dimension whose sign varies over the block
+        head = np.zeros((shape.vocab, shape.d_model), dtype=np.float32)
+        head[a_id, dim] = head[b_id, dim] = 0.75
+
+        def tensor(name, layer=0, head=head):
+            return head if name == "lm_head" else src.tensor_f32(name, layer)
+
+        m = vo.Model(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn, shape.vocab,
+                     shape.rope_base, shape.rms_eps, tensor=tensor)
+        cache = vo.prefill(m, prompt, 64)
+        lg, _, _ = vo.forward_blocks(m, [cache], [block], [vo.chain_parents(24)])
+        s = lg[0][:, a_id]
+        if (s > 0).any() and (s < 0).any():
+            break
+    assert np.array_equal(s, lg[0][:, b_id]) and (s > 0).any() and (s < 0).any()
+    am, gap = vo._argmax_and_gap(lg[0])
+    assert np.all(gap == 0.0)
+    assert np.array_equal(am, np.where(s > 0, a_id, 0))
+    # acceptance follows the lowest-id choice: drafting the other member of the tie is rejected
+    want0 = cache.next_tok
+    assert want0 in (a_id, 0)
+    first = vo.verify(m, [cache], [np.array([want0])])[0]              # the target's choice after candidate 0
+    t1 = int(first.argmax[0])
+    assert first.top2_gap[0] == 0.0 and t1 in (a_id, 0)
+    other = b_id if t1 == a_id else 1                                  # the higher-id member of the same tie
+    r_good = vo.verify(m, [cache], [np.array([want0, t1])])[0]
+    r_other = vo.verify(m, [cache], [np.array([want0, other])])[0]
+    assert r_good.accept_len == 2 and r_other.accept_len == 1 and r_other.bonus_token == t1
+
+
+# ---------------------------------------------------------------------------
 # whole forward against an independently assembled one (padded + dense mask, torch ops)
 # ---------------------------------------------------------------------------
 
@@ -257,12 +323,14 @@ def torch_padded_forward(shape, weights, prefix_tok_lists, block_tok_lists, pare
         z = torch.complex(x[..., :hd // 2], x[..., hd // 2:]) * rot[:, :, None, :]
         return torch.cat([z.real, z.imag], dim=-1)
 
-    def norm(x):
+    def norm(x, gain_key=None):
+        if gain_key in W:                                # non-unit gains: the library's own RMSNorm
+            return torch.nn.functional.rms_norm(x, (x.shape[-1],), weight=W[gain_key], eps=shape.rms_eps)
         return x * torch.rsqrt(x.pow(2).mean(-1, keepdim=True) + shape.rms_eps)
 
     h = W["embed"][ids]
     for l in range(shape.n_layers):
-        x = norm(h)
+        x = norm(h, f"g_attn{l}")
         q = rotate(torch.nn.functional.linear(x, W[f"wq{l}"]).view(B, T, Hq, hd))
         k = rotate(torch.nn.functional.linear(x, W[f"wk{l}"]).view(B, T, Hkv, hd))
         v = torch.nn.functional.linear(x, W[f"wv{l}"]).view(B, T, Hkv, hd)
@@ -277,32 +345,42 @@ def torch_padded_forward(shape, weights, prefix_tok_lists, block_tok_lists, pare
         s = torch.einsum("bthd,bshd->bhts", q, k) / math.sqrt(hd) + bias
         o = torch.einsum("bhts,bshd->bthd", torch.softmax(s, dim=-1), v).reshape(B, T, Hq * hd)
         h = h + torch.nn.functional.linear(o, W[f"wo{l}"])
-        x = norm(h)
+        x = norm(h, f"g_ffn{l}")
         h = h + torch.nn.functional.linear(
             torch.nn.functional.silu(torch.nn.functional.linear(x, W[f"wg{l}"])) * torch.nn.functional.linear(x, W[f"wu{l}"]),
             W[f"wd{l}"])
-    logits = torch.nn.functional.linear(norm(h), W["lm_head"])
+    logits = torch.nn.functional.linear(norm(h, "g_final"), W["lm_head"])
     return [logits[b, Ps[b]:Ps[b] + ns[b]].numpy() for b in range(B)]
 
 
-def _weights_dict(shape, seed):
+def _weights_dict(shape, seed, gains=False):
     src = synth.WeightSource(shape, seed)
     W = {"embed": src.tensor_f32("embed"), "lm_head": src.tensor_f32("lm_head")}
     for l in range(shape.n_layers):
         for nme in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
             W[f"{nme}{l}"] = src.tensor_f32(nme, l)
+        if gains:
+            W[f"g_attn{l}"], W[f"g_ffn{l}"] = src.gain("norm_attn", l), src.gain("norm_ffn", l)
+    if gains:
+        W["g_final"] = src.gain("norm_final")
     return W
 
 
+@pytest.mark.parametrize("gains", [False, True], ids=["unit-gains", "seeded-gains"])
 @pytest.mark.parametrize("shape", [synth.TINY, synth.MINI_BF16.with_layers(2)], ids=["mha-hd64", "gqa-hd128"])
-def test_ragged_oracle_equals_padded_dense_torch_forward(shape):
+def test_ragged_oracle_equals_padded_dense_torch_forward(shape, gains):
     """Heterogeneous lengths in one batch, chain and tree blocks: the ragged per-request oracle
-    equals the padded, densely masked batch forward (independent code: torch ops, complex RoPE)."""
+    equals the padded, densely masked batch forward (independent code: torch ops, complex RoPE;
+    with seeded non-unit norm gains the reference norm is torch's rms_norm routine, so a gain that
+    is dropped, applied at the wrong norm or taken from the wrong layer shows)."""
     seed = 21
     kvb = shape.dtype == "bf16"
-    m = oracle_model(shape, seed)
+    m = oracle_model(shape, seed, gains=gains)
     assert m.kv_bf16 == kvb
-    W = _weights_dict(shape, seed)
+    W = _weights_dict(shape, seed, gains)
+    if gains:                                            # the three gain vectors of a layer differ, and so do the layers'
+        assert not np.allclose(W["g_attn0"], W["g_ffn0"]) and not np.allclose(W["g_attn0"], W["g_attn1"])
+        assert not np.allclose(W["g_final"], W["g_attn0"]) and W["g_final"].min() >= 0.5 and W["g_final"].max() < 1.5
     lens = [5, 23, 12]
     prefixes = [synth.rng.uniform_i32(seed, 100 + b, P, 0, shape.vocab) for b, P in enumerate(lens)]
     caches = [vo.prefill(m, p, 64) for p in prefixes]
