@@ -69,7 +69,7 @@ int64_t sev_sched_verify_estimate(const sev_sched *s);
  *     t_verify ~= depth * t_draft_fwd + rtt :
  * depth = (t_verify - rtt) / t_draft_fwd rounded to nearest (halves up), clamped to
  * [min_depth, max_depth]; min_depth if t_verify <= rtt.  Returns the depth, or a negative status for
- * t_draft_fwd_us < 1, min_depth < 1 or max_depth < min_depth.  (The paper's example: verification
+ * t_draft_fwd_us < 1, a negative t_verify_us or rtt_us, min_depth < 1 or max_depth < min_depth.  (The paper's example: verification
  * 94.2 ms, 11 ms per draft pass: depth 7 at 15 ms RTT, 5 at 40 ms, 4 at 50 ms.) */
 int sev_sched_calibrate_depth(int64_t t_verify_us, int64_t t_draft_fwd_us, int64_t rtt_us, int32_t min_depth, int32_t max_depth);
 

@@ -42,5 +42,42 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized(out_dir: str) -> str:
+    """Builds tests/host_sanitize/driver.cpp together with every source of the library and synth/rng.c, with
+    AddressSanitizer and UndefinedBehaviorSanitizer on the HOST code only (device code is compiled as usual: the GPU
+    sanitizers are not used), into out_dir/host_sanitize.  The program needs no GPU."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    clang = os.path.join(os.path.dirname(os.path.realpath(hipcc)), "..", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/llvm/bin/clang"
+    root = os.path.dirname(HERE)
+    os.makedirs(out_dir, exist_ok=True)
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-g"]
+    host_only = [x for f in san for x in ("-Xarch_host", f)]
+    jobs = []
+    for s in SOURCES:
+        o = os.path.join(out_dir, os.path.splitext(s)[0] + ".o")
+        if s.endswith(".hip"):
+            cmd = [hipcc, "--offload-arch=gfx950", "-O1", "-std=c++17", *host_only, "-Xclang", "-target-feature", "-Xclang",
+                   "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-Wno-unused-value", "-Wno-unused-result",
+                   "-Wno-pass-failed", "-c", os.path.join(CSRC, s), "-o", o]
+        else:
+            cmd = [clang + "++", "-std=c++17", "-O1", *san, "-c", os.path.join(CSRC, s), "-o", o]
+        jobs.append((o, cmd))
+    jobs.append((os.path.join(out_dir, "rng.o"), [clang, "-O1", *san, "-c", os.path.join(root, "synth", "rng.c"), "-o",
+                                                  os.path.join(out_dir, "rng.o")]))
+    jobs.append((os.path.join(out_dir, "driver.o"), [clang + "++", "-std=c++17", "-O1", *san, "-c",
+                                                     os.path.join(root, "tests", "host_sanitize", "driver.cpp"), "-o",
+                                                     os.path.join(out_dir, "driver.o")]))
+    procs = [(o, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)) for o, cmd in jobs]
+    for o, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"building {o} failed:\n{out}")
+    exe = os.path.join(out_dir, "host_sanitize")
+    subprocess.check_call([hipcc, "-fsanitize=address", "-fsanitize=undefined", *[o for o, _ in jobs], "-o", exe, "-lm"])
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True))

@@ -384,55 +384,6 @@ __device__ __forceinline__ void ssq_commit(const GemmArgs &g, float (*red)[128],
     }
 }
 
-#ifdef SEV_TRACE
-// timing probes for tuning experiments (never compiled into the library proper)
-__device__ unsigned long long *g_trace;
-__device__ unsigned g_trace_pos, g_trace_cap;
-__device__ __forceinline__ unsigned long long sev_trace_now() {     // pinned in program order (a plain clock read may be moved)
-    unsigned long long t;
-    asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t) : : "memory");
-    return t;
-}
-#define SEV_TRACE_T(var) const unsigned long long var = sev_trace_now()
-#define SEV_TRACE_FIX(i) trf[i] = sev_trace_now()
-extern "C" int sev_trace_begin(int cap) {
-    unsigned long long *buf;
-    if (hipMalloc(&buf, (size_t)cap * 64) != hipSuccess) return -1;
-    unsigned zero = 0, c = (unsigned)cap;
-    hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &buf, sizeof(buf));
-    hipMemcpyToSymbol(HIP_SYMBOL(g_trace_pos), &zero, 4);
-    hipMemcpyToSymbol(HIP_SYMBOL(g_trace_cap), &c, 4);
-    return 0;
-}
-extern "C" int sev_trace_read(unsigned long long *host, int cap) {
-    unsigned long long *buf; unsigned n;
-    hipDeviceSynchronize();
-    hipMemcpyFromSymbol(&buf, HIP_SYMBOL(g_trace), sizeof(buf));
-    hipMemcpyFromSymbol(&n, HIP_SYMBOL(g_trace_pos), 4);
-    if ((int)n > cap) n = cap;
-    hipMemcpy(host, buf, (size_t)n * 64, hipMemcpyDeviceToHost);
-    unsigned zero = 0;
-    hipMemcpyToSymbol(HIP_SYMBOL(g_trace_pos), &zero, 4);
-    return (int)n;
-}
-#define SEV_TRACE_END(t4)                                                                                              \
-    if (threadIdx.x == 0 && g_trace) {                                                                                 \
-        SEV_TRACE_T(tr_e);                                                                                             \
-        const unsigned i_ = atomicAdd(&g_trace_pos, 1u);                                                               \
-        if (i_ < g_trace_cap) {                                                                                        \
-            unsigned long long *t_ = g_trace + (size_t)i_ * 8;                                                         \
-            t_[0] = (unsigned long long)EPI | ((unsigned long long)g.N << 8) | ((unsigned long long)g.splits << 40);   \
-            t_[1] = blockIdx.x | ((unsigned long long)(t4) << 32);                                                     \
-            t_[2] = (unsigned long long)__builtin_amdgcn_s_getreg(20 | (31 << 11));                                    \
-            t_[3] = tr0; t_[4] = tr1; t_[5] = tr2; t_[6] = tr_e; t_[7] = n;                                            \
-        }                                                                                                              \
-    }
-#else
-#define SEV_TRACE_T(var)
-#define SEV_TRACE_FIX(i)
-#define SEV_TRACE_END(t4)
-#endif
-
 // Kernel arguments live in memory and are fetched with scalar loads where the compiler first needs
 // them; an argument block of several cache lines can then cost one memory latency per line, one after
 // the other, in the middle of the kernel.  Naming one field of every line at the kernel's entry makes
@@ -455,7 +406,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     static_assert(KS * MT % 2 == 0, "a stage of activations must be a whole number of 4 KiB");
     extern __shared__ u32x4 xs[];                       // [2 buffers][KS k-steps][MT][2 planes][64 lanes]
     __shared__ float red[4][128];
-    SEV_TRACE_T(tr0);
     constexpr int STAGE_U4 = KS * MT * 2 * 64;          // uint4 per stage
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // Block index decode, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, each with its
@@ -584,7 +534,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     else if constexpr (EPI == EPI_ARGMAX) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.lm_val), "s"(g.logits));
     else SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.act));
     __syncthreads();
-    SEV_TRACE_T(tr1);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -665,7 +614,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     };
     for (int base = 0; base + PF < n_pad; base += PF) group(base, std::true_type{});
     group(n_pad - PF, std::false_type{});
-    SEV_TRACE_T(tr2);
 
     // ------------------------------------------------------------------ split-K: hand the slice to the fix-up kernel
     if (g.splits > 1) {
@@ -681,7 +629,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
                 for (int j = 0; j < 4; ++j)
                     mine[((a * MT + b) * 4 + j) * 64] =
                         make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
-        SEV_TRACE_END(0);
         return;
     }
 
@@ -744,7 +691,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
             }
         }
     }
-    SEV_TRACE_END(1);
 }
 
 // Split-K fix-up: block (column group cg, row tile mt, a) of 4 waves; wave w sums the S slices of the
@@ -754,7 +700,6 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, con
                                                          int col_groups_, int m_blocks_, int geo_, int n_tiles_, int M_, int N_, int heads_,
                                                          GemmArgs g) {
     __shared__ float red[4][128];
-    SEV_TRACE_T(tr0);
     // leading scalars (preloaded at wave launch): everything the first loads need; pa_ / pb_ are the residual stream and
     // the gains (EPI_RESID) or the rotary table and the rows' cache locations (EPI_QKV); geo_ = MT | NT << 8 | S << 16,
     // heads_ = query heads | KV heads << 16
@@ -783,9 +728,6 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, con
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
     const bool live = T < g.n_tiles;
     float ss = 0.f;
-#ifdef SEV_TRACE
-    unsigned long long trf[3] = {0, 0, 0};
-#endif
     if (live) {
         const TilePre pre = tile_pre<EPI>(g, T, m, nsub);       // issued ahead of the slice loads
         for (int s0 = 0; s0 < g.splits; s0 += 8) {
@@ -809,25 +751,13 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, con
                     }
                 }
         }
-        SEV_TRACE_FIX(1);
         ss = tile_epilogue<EPI>(g, acc, T, m, nsub, pre);
     }
-    SEV_TRACE_FIX(2);
     if constexpr (EPI == EPI_RESID) {
         ss += __shfl_xor(ss, 32);
         if (lane < 32) red[wave][mrow] = ss;
         ssq_commit(g, red, 32, mt * 32, cg == 0 && a == 0);
     }
-#ifdef SEV_TRACE
-    if (threadIdx.x == 0 && g_trace) {
-        SEV_TRACE_T(tr_e);
-        const unsigned i_ = atomicAdd(&g_trace_pos, 1u);
-        if (i_ < g_trace_cap) {
-            unsigned long long *t_ = g_trace + (size_t)i_ * 8;
-            t_[0] = 200 + EPI; t_[1] = blockIdx.x; t_[2] = 0; t_[3] = tr0; t_[4] = trf[1]; t_[5] = trf[2]; t_[6] = tr_e; t_[7] = g.splits;
-        }
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -891,7 +821,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     g.Hkv = heads_ >> 16;
     g.v_offset = v_off_;
     extern __shared__ float lds[];                    // WAVES merge slots: 64 accumulator registers + max + sum per lane
-    SEV_TRACE_T(tr0);
     const int item = blockIdx.x, kvh = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar: loop bounds stay uniform
     // everything the block needs to know comes from two 16-byte loads and one page-id load, all independent
@@ -960,7 +889,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[t][r] = 0.f;
     float mrun = -INFINITY, lrun = 0.f;
-    SEV_TRACE_T(tr1);
 
     auto pair_step = [&](int i, auto prefetch_tag) {
         constexpr bool PREFETCH = decltype(prefetch_tag)::value;
@@ -1034,11 +962,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     };
     for (int i = 0; i + 1 < my_pairs; ++i) pair_step(i, std::true_type{});
     if (my_pairs > 0) pair_step(my_pairs - 1, std::false_type{});
-    SEV_TRACE_T(tr2);
-#ifdef SEV_TRACE
-    __shared__ unsigned long long wave_t2[8];
-    if (lane == 0) wave_t2[wave] = tr2;
-#endif
 
     // ---- merge the waves through LDS in one step: every wave publishes its (max, sum, O) in the
     // accumulators' own register layout; then wave w reduces register quads [w * QW, (w + 1) * QW) of all
@@ -1067,7 +990,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
         l += slotL[v * 64 + lane] * wsc[v];
     }
     l += __shfl_xor(l, 32);                             // the other half of the row's keys
-    SEV_TRACE_T(tr3);
     constexpr int QW = 16 / WAVES;
     const float inv = DIRECT ? 1.0f / l : 1.0f;
     const size_t base = ((size_t)item * g.Hkv + kvh) * 32;
@@ -1097,20 +1019,6 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
             *(float4 *)(att_o + (base + qrow) * 128 + dim) = make_float4(o[0], o[1], o[2], o[3]);
         }
     }
-#ifdef SEV_TRACE
-    if (threadIdx.x == 0 && g_trace) {
-        SEV_TRACE_T(tr_e);
-        const unsigned i_ = atomicAdd(&g_trace_pos, 1u);
-        if (i_ < g_trace_cap) {
-            unsigned long long *t_ = g_trace + (size_t)i_ * 8;
-            t_[0] = 100; t_[1] = blockIdx.x | ((unsigned long long)blockIdx.y << 32);
-            t_[2] = tr3 - tr1;
-            unsigned long long lo_ = ~0ull, hi_ = 0;
-            for (int w = 0; w < WAVES; ++w) { lo_ = wave_t2[w] < lo_ ? wave_t2[w] : lo_; hi_ = wave_t2[w] > hi_ ? wave_t2[w] : hi_; }
-            t_[3] = tr0; t_[4] = tr1; t_[5] = tr2; t_[6] = tr_e; t_[7] = npages | ((lo_ - tr1) << 16) | ((hi_ - tr1) << 40);
-        }
-    }
-#endif
 }
 
 // cross-chunk merge + normalisation; writes the attention output as hi/lo fragments for the O projection.
@@ -1179,10 +1087,9 @@ struct GemmCfg {
 enum { G_QKV = 0, G_O, G_GU, G_DOWN, G_LM };
 
 // Tile configuration of one GEMM.  Row tiles per block MT (weights are re-read through L2 by each row
-// block), column tiles per wave NT, split-K slices S, prefetch depth PF.  Environment variables
-// SEV_TUNE_QKV / _O / _GU / _DOWN / _LM = "MT,NT,S,PF" override the choice (tuning experiments).
-static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size_t part_elems) {
-    static const char *names[] = {"SEV_TUNE_QKV", "SEV_TUNE_O", "SEV_TUNE_GU", "SEV_TUNE_DOWN", "SEV_TUNE_LM"};
+// block), column tiles per wave NT, split-K slices S, prefetch depth PF.  The handle's tuning overrides
+// (struct Tune: read from the environment when the handle was created) replace the choice in experiments.
+static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size_t part_elems, const Tune &tune) {
     GemmCfg c;
     c.MT = (which == G_LM && m_tiles >= 3) ? 4 : (m_tiles >= 2 ? 2 : 1);
     c.NT = (n_tiles % 2 == 0) ? 2 : 1;
@@ -1210,9 +1117,9 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
         c.NT = 1;
         pick_s();
     }
-    if (const char *e = getenv(names[which])) {          // "MT,NT,S,PF"; S = 0 keeps the automatic split
-        int mt, nt, sp, pf;
-        if (sscanf(e, "%d,%d,%d,%d", &mt, &nt, &sp, &pf) == 4 && (mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2 || (nt == 4 && mt == 4 && pf == 4)) &&
+    if (tune.has_gemm[which]) {                          // "MT,NT,S,PF"; S = 0 keeps the automatic split
+        const int mt = tune.gemm[which][0], nt = tune.gemm[which][1], sp = tune.gemm[which][2], pf = tune.gemm[which][3];
+        if ((mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2 || (nt == 4 && mt == 4 && pf == 4)) &&
             sp >= 0 && sp <= 32 && (pf == 4 || (pf == 6 && mt <= 2))) {
             c.MT = std::min(mt, m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1));
             c.NT = (nt == 4 && c.MT != 4) ? 2 : nt;
@@ -1233,8 +1140,8 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
         for (int t = 4 * c.NT - 1; t >= 3 * c.NT + 1; --t)
             if (blocks_t(4 * c.NT) < 256 && blocks_t(t) <= 256 && blocks_t(t) > blocks_t(c.T)) c.T = t;
     }
-    if (const char *e = getenv("SEV_TUNE_TPB")) {        // tuning experiments: tiles per block of the gate/up GEMM
-        const int t = atoi(e);
+    if (tune.tpb) {                                      // tuning experiments: tiles per block of the gate/up GEMM
+        const int t = tune.tpb;
         if (which == G_GU && c.S == 1 && t >= 3 * c.NT + 1 && t <= 4 * c.NT) c.T = t;
     }
     // the exchange buffer holds S slices of (padded columns) x (padded rows)
@@ -1292,11 +1199,11 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
         hipLaunchKernelGGL(embed_norm_kernel, dim3(rows), dim3(256), 0, st, (const uint16_t *)(m->arena + m->off_embed),
                            kv->plan.row_tok, Gp(m->layers[0].g_attn), kv->h, xa, kv->ssq[1], kv->ssq[0], d.d_model, m_tiles);
     }
-    const GemmCfg pq = choose_cfg(G_QKV, m_tiles_real, m->n_qkv / 32, d.d_model / 16, kv->part_elems);
-    const GemmCfg po = choose_cfg(G_O, m_tiles_real, d.d_model / 32, m->q_dim / 16, kv->part_elems);
-    const GemmCfg pg = choose_cfg(G_GU, m_tiles_real, d.d_ffn / 16, d.d_model / 16, kv->part_elems);
-    const GemmCfg pd = choose_cfg(G_DOWN, m_tiles_real, d.d_model / 32, d.d_ffn / 16, kv->part_elems);
-    const GemmCfg pl = choose_cfg(G_LM, m_tiles_real, d.vocab / 32, d.d_model / 16, kv->part_elems);
+    const GemmCfg pq = choose_cfg(G_QKV, m_tiles_real, m->n_qkv / 32, d.d_model / 16, kv->part_elems, kv->tune);
+    const GemmCfg po = choose_cfg(G_O, m_tiles_real, d.d_model / 32, m->q_dim / 16, kv->part_elems, kv->tune);
+    const GemmCfg pg = choose_cfg(G_GU, m_tiles_real, d.d_ffn / 16, d.d_model / 16, kv->part_elems, kv->tune);
+    const GemmCfg pd = choose_cfg(G_DOWN, m_tiles_real, d.d_model / 32, d.d_ffn / 16, kv->part_elems, kv->tune);
+    const GemmCfg pl = choose_cfg(G_LM, m_tiles_real, d.vocab / 32, d.d_model / 16, kv->part_elems, kv->tune);
     GemmArgs base;
     memset(&base, 0, sizeof(base));
     base.m_tiles_total = m_tiles;

@@ -198,6 +198,16 @@ KvGeom sev_kv_geom(const sev_kv *kv) {
 
 #define ATT_ITEMS_CAP 4096
 
+static void read_tune(Tune *t) {
+    static const char *names[5] = {"SEV_TUNE_QKV", "SEV_TUNE_O", "SEV_TUNE_GU", "SEV_TUNE_DOWN", "SEV_TUNE_LM"};
+    memset(t, 0, sizeof(*t));
+    for (int i = 0; i < 5; ++i)
+        if (const char *e = getenv(names[i]))
+            t->has_gemm[i] = sscanf(e, "%d,%d,%d,%d", &t->gemm[i][0], &t->gemm[i][1], &t->gemm[i][2], &t->gemm[i][3]) == 4;
+    if (const char *e = getenv("SEV_TUNE_TPB")) t->tpb = atoi(e);
+    if (const char *e = getenv("SEV_TUNE_CP")) t->cp = atoi(e);
+}
+
 extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows, int64_t n_pages, int page_size,
                              void *pool, size_t pool_bytes, sev_kv **out) {
     if (!out) return sev_fail(SEV_EINVAL, "null output handle");
@@ -223,6 +233,7 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->v_offset = (size_t)n_pages * d.n_kv_heads * kv_block_bytes(d);
     kv->layer_stride = 2 * kv->v_offset;
     kv->max_pages_per_req = (int)n_pages;
+    read_tune(&kv->tune);
     kv->prof_on = 0;
     memset(kv->prof_ms, 0, sizeof(kv->prof_ms));
     memset(kv->prof_n, 0, sizeof(kv->prof_n));
@@ -517,7 +528,7 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     int64_t max_pages = 0;
     for (int b = 0; b < pa.B; ++b)
         max_pages = std::max<int64_t>(max_pages, (std::max(pa.prefix[b] + pa.nd[b], pa.pad_tokens) + SEV_PAGE - 1) / SEV_PAGE);
-    if (!getenv("SEV_TUNE_CP") && max_pages <= 64 && total_groups * d.n_kv_heads * 2 >= n_cu &&
+    if (!kv->tune.cp && max_pages <= 64 && total_groups * d.n_kv_heads * 2 >= n_cu &&
         total_groups <= kv->max_items) {
         *direct = true;
         *n_items = (int)total_groups;
@@ -528,10 +539,7 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     for (int64_t c = 8; c <= SEV_ATT_MAX_CHUNK; c += 8)
         if (items_for(c) * d.n_kv_heads <= (int64_t)n_cu) { cp = c; break; }
     if (!cp) cp = 64;
-    if (const char *e = getenv("SEV_TUNE_CP")) {        // tuning experiments: pages per attention chunk
-        const int v = atoi(e);
-        if (v >= 2 && v <= SEV_ATT_MAX_CHUNK) cp = v;
-    }
+    if (kv->tune.cp >= 2 && kv->tune.cp <= SEV_ATT_MAX_CHUNK) cp = kv->tune.cp;      // tuning experiments: pages per attention chunk
     for (;; cp = std::min<int64_t>(cp * 2, SEV_ATT_MAX_CHUNK)) {
         const int64_t items = items_for(cp);
         if (items <= kv->max_items) {

@@ -84,8 +84,18 @@ struct ProfSpan {
     int cls;
 };
 
+// Tile-shape overrides for tuning experiments, read from the environment ONCE, when the handle is created:
+// SEV_TUNE_QKV / _O / _GU / _DOWN / _LM = "MT,NT,S,PF" (S = 0 keeps the automatic split), SEV_TUNE_TPB = column tiles
+// per block of the gate/up GEMM, SEV_TUNE_CP = pages per attention chunk.  Unset (the normal case): all zero.
+struct Tune {
+    int gemm[5][4];
+    bool has_gemm[5];
+    int tpb, cp;
+};
+
 struct sev_kv {
     const sev_model *model;
+    Tune tune;
     int max_req, max_rows, page_size;
     int64_t n_pages;
     char *pool;

@@ -115,9 +115,11 @@ extern "C" int64_t sev_sched_verify_estimate(const sev_sched *s) { return (s && 
 extern "C" int sev_sched_calibrate_depth(int64_t t_verify_us, int64_t t_draft_fwd_us, int64_t rtt_us, int32_t min_depth, int32_t max_depth) {
     if (t_draft_fwd_us < 1) return sev_fail(SEV_EINVAL, "t_draft_fwd_us must be positive");
     if (min_depth < 1 || max_depth < min_depth) return sev_fail(SEV_EINVAL, "need 1 <= min_depth <= max_depth");
-    const int64_t budget = t_verify_us - rtt_us;                  // time left for drafting
+    if (t_verify_us < 0 || rtt_us < 0) return sev_fail(SEV_EINVAL, "times must not be negative");
+    const int64_t budget = t_verify_us - rtt_us;                  // time left for drafting (both terms >= 0: no overflow)
     if (budget <= 0) return min_depth;
-    const int64_t depth = (2 * budget + t_draft_fwd_us) / (2 * t_draft_fwd_us);   // nearest, halves up
+    const int64_t whole = budget / t_draft_fwd_us, rem = budget % t_draft_fwd_us;
+    const int64_t depth = whole + (rem >= t_draft_fwd_us - rem ? 1 : 0);          // nearest, halves up, without doubling anything
     return (int)std::min<int64_t>(std::max<int64_t>(depth, min_depth), max_depth);
 }
 
