@@ -241,6 +241,18 @@ typedef struct {
 
 int sev_verify_sample(const sev_model *weights, sev_kv *kv_cache, const sev_sample_args *args, void *stream);
 
+/* sev_verify_sample for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same step, but the block's logits -- the one scratch buffer
+ * sev_verify_sample takes from its caller -- live in a static device array of SEV_STATIC_SCRATCH_BYTES inside the
+ * library (one copy per GPU, held until the process ends).  args->logits_ws must be NULL; everything else is as in
+ * sev_verify_sample, outputs included (the logits themselves are not returned).  The call makes no hipMalloc /
+ * hipFree and uses no allocating library routine; it needs sev_profile_enable to be off (SEV_ESTATE otherwise).
+ * SEV_ENOSPACE if (sum of draft lengths) * vocab * 4 bytes exceeds SEV_STATIC_SCRATCH_BYTES.
+ * All calls on one GPU share the array: calls that overlap on one GPU (different streams, different handles) race;
+ * the array keeps the previous call's contents, and every row a call reads it has written first. */
+#define SEV_STATIC_SCRATCH_BYTES (64u << 20)
+int sev_verify_sample_static(const sev_model *weights, sev_kv *kv_cache, const sev_sample_args *args, void *stream);
+
 /* Prefill: the step before verification (appendix "Additional Details on
  * Evaluation Setup": the prompt is prefilled on the server before decoding starts
  * and is excluded from the reported metrics).  Appends n_tokens[b] tokens to the

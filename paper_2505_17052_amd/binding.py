@@ -72,6 +72,7 @@ def lib():
         "sev_verify": (i32, [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp]),
         "sev_verify_ex": (i32, [vp, vp, C.POINTER(VerifyArgs), vp]),
         "sev_verify_sample": (i32, [vp, vp, C.POINTER(SampleArgs), vp]),
+        "sev_verify_sample_static": (i32, [vp, vp, C.POINTER(SampleArgs), vp]),
         "sev_prefill": (i32, [vp, vp, vp, vp, vp, vp, i32, i32, vp]),
         "sev_kv_commit": (i32, [vp, vp, i32, vp]),
         "sev_kv_rollback": (i32, [vp, vp, i32, vp]),
@@ -283,6 +284,18 @@ def verify_sample(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Te
                    float(temperature), _dp(out["logits"]), _dp(out["accept_len"]), _dp(out["emitted_token"]),
                    _dp(out["accept_path"]))
     _check(lib().sev_verify_sample(model.handle, kv.handle, C.byref(a), _stream_ptr()), "sev_verify_sample")
+    return out
+
+
+def verify_sample_static(model: Model, kv: KVCache, prefix_lens, draft_tokens: torch.Tensor, k_max: int, draft_probs: torch.Tensor,
+                         u_accept: torch.Tensor, u_emit: torch.Tensor, temperature: float, out: dict, slots=None, draft_lens=None,
+                         parents: torch.Tensor = None):
+    """sev_verify_sample_static: as verify_sample, with the logits in the library's static scratch.  `out` holds the
+    caller's output tensors (accept_len, emitted_token, accept_path): this call allocates nothing on the device."""
+    pl, sl, dl = _host_i32(prefix_lens), _host_i32(slots), _host_i32(draft_lens)
+    a = SampleArgs(len(pl), k_max, _hp(sl), _hp(pl), _hp(dl), _dp(draft_tokens), _dp(parents), _dp(draft_probs), _dp(u_accept), _dp(u_emit),
+                   float(temperature), None, _dp(out["accept_len"]), _dp(out["emitted_token"]), _dp(out["accept_path"]))
+    _check(lib().sev_verify_sample_static(model.handle, kv.handle, C.byref(a), _stream_ptr()), "sev_verify_sample_static")
     return out
 
 

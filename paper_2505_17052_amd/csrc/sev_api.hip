@@ -28,6 +28,8 @@ extern "C" const char *sev_last_error(void) { return g_err; }
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+static int static_scratch(void **out);      // device address of the static scratch array on the current device
+
 // ---------------------------------------------------------------------------
 // model
 // ---------------------------------------------------------------------------
@@ -206,6 +208,7 @@ static void read_tune(Tune *t) {
             t->has_gemm[i] = sscanf(e, "%d,%d,%d,%d", &t->gemm[i][0], &t->gemm[i][1], &t->gemm[i][2], &t->gemm[i][3]) == 4;
     if (const char *e = getenv("SEV_TUNE_TPB")) t->tpb = atoi(e);
     if (const char *e = getenv("SEV_TUNE_CP")) t->cp = atoi(e);
+    if (const char *e = getenv("SEV_TUNE_RS")) t->rs = atoi(e);
 }
 
 extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows, int64_t n_pages, int page_size,
@@ -338,6 +341,11 @@ extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows,
     kv->ssq[0] = (unsigned long long *)(w + o_ssq);
     kv->ssq[1] = kv->ssq[0] + rows_pad;
     launch_fill_i32(kv->next_tok, -1, max_requests, 0);
+    {   // set-up for sev_verify_sample_static: look the static scratch up for this device now (a failure only
+        // matters to that entry point, which reports it)
+        void *unused = nullptr;
+        (void)static_scratch(&unused);
+    }
     e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         hipFree(kv->ws);
@@ -674,6 +682,55 @@ extern "C" int sev_verify_sample(const sev_model *m, sev_kv *kv, const sev_sampl
     c.accept_len = a->accept_len; c.bonus_token = a->emitted_token; c.accept_path = a->accept_path; c.logits = a->logits_ws;
     c.draft_probs = a->draft_probs; c.u_accept = a->u_accept; c.u_emit = a->u_emit; c.temperature = a->temperature;
     return run_block(m, kv, c, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------
+// stochastic verification without a caller workspace: the block's logits live in a static device array
+// ---------------------------------------------------------------------------
+// File-scope device memory, one copy per GPU, held until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: the device address is looked up once per device (with that device current) and every
+// kernel argument below uses the looked-up pointer.
+static __device__ __align__(256) unsigned char sev_static_scratch[SEV_STATIC_SCRATCH_BYTES];
+
+#define SEV_MAX_DEVICES 64
+static void *g_scratch_ptr[SEV_MAX_DEVICES];     // per device; written once (same value from any thread)
+
+static int static_scratch(void **out) {
+    int dev = -1;
+    SEV_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= SEV_MAX_DEVICES) return sev_fail(SEV_EINVAL, "device %d beyond the %d the static scratch table covers", dev, SEV_MAX_DEVICES);
+    void *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        SEV_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(sev_static_scratch)));
+        if (!p || ((uintptr_t)p & 255)) return sev_fail(SEV_EHIP, "static scratch: bad device address %p", p);
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return SEV_OK;
+}
+
+extern "C" int sev_verify_sample_static(const sev_model *m, sev_kv *kv, const sev_sample_args *a, void *stream) {
+    if (!m || !kv || !a) return sev_fail(SEV_EINVAL, "null argument");
+    if (a->B < 1 || a->B > SEV_MAX_BATCH) return sev_fail(SEV_EINVAL, "B=%d outside 1..%d", a->B, SEV_MAX_BATCH);
+    if (a->k_max < 1 || a->k_max > SEV_MAX_DRAFT) return sev_fail(SEV_EINVAL, "k=%d outside 1..%d", a->k_max, SEV_MAX_DRAFT);
+    if (a->logits_ws) return sev_fail(SEV_EINVAL, "logits_ws must be NULL: this entry point keeps the logits in the library's static scratch");
+    if (kv->prof_on) return sev_fail(SEV_ESTATE, "per-kernel profiling creates events; switch it off for the entry point that allocates nothing");
+    int64_t rows = 0;
+    for (int b = 0; b < a->B; ++b) {
+        const int n = a->draft_lens ? a->draft_lens[b] : a->k_max;
+        if (n < 1 || n > a->k_max) return sev_fail(SEV_EINVAL, "request %d: draft length %d outside 1..%d", b, n, a->k_max);
+        rows += n;
+    }
+    const size_t need = (size_t)rows * (size_t)m->d.vocab * sizeof(float);
+    if (need > (size_t)SEV_STATIC_SCRATCH_BYTES)
+        return sev_fail(SEV_ENOSPACE, "%lld rows x %d logits need %zu bytes; the static scratch holds %zu", (long long)rows, m->d.vocab, need,
+                        (size_t)SEV_STATIC_SCRATCH_BYTES);
+    void *scratch = nullptr;
+    const int rc = static_scratch(&scratch);
+    if (rc != SEV_OK) return rc;
+    sev_sample_args b = *a;
+    b.logits_ws = (float *)scratch;            // every row the sampling kernels read is written by this call's LM head first
+    return sev_verify_sample(m, kv, &b, stream);
 }
 
 // Prefill: long chains are fed through the same forward pass in chunks that fit the row budget, each

@@ -69,6 +69,7 @@ static void abi_validation() {
     sev_sample_args sa;
     memset(&sa, 0, sizeof(sa));
     EXPECT(sev_verify_sample(nullptr, nullptr, &sa, nullptr) == SEV_EINVAL);
+    EXPECT(sev_verify_sample_static(nullptr, nullptr, &sa, nullptr) == SEV_EINVAL);
     EXPECT(sev_prefill(nullptr, nullptr, nullptr, one, one, one, 1, 1, nullptr) == SEV_EINVAL);
     EXPECT(sev_kv_commit(nullptr, nullptr, 1, nullptr) == SEV_EINVAL);
     EXPECT(sev_kv_rollback(nullptr, nullptr, 1, nullptr) == SEV_EINVAL);
