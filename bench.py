@@ -64,23 +64,34 @@ def main():
     batch.fill_synthetic(wl.seed, lens, [int(r.prefix_tokens[-1]) for r in reqs])
     nt0 = [batch.kv.get_state(b)[1] for b in range(B)]
 
-    # drafts: the model's own greedy continuation (k-1 single-token verify+commit rounds through the
-    # library), then each position replaced by a random id with probability p
-    g = np.zeros((B, k), dtype=np.int32)
-    g[:, 0] = nt0
-    cur = list(lens)
-    for i in range(1, k):
-        a, bt = sev.verify(model, batch.kv, cur, torch.tensor(g[:, i - 1:i].copy(), device="cuda"), None, B, 1)
-        sev.kv_commit(batch.kv, None, B)
-        torch.cuda.synchronize()
-        assert int(a.min()) == 1
-        g[:, i] = bt.cpu().numpy()
-        cur = [c + 1 for c in cur]
-    drafts = g.copy()
-    for b, r in enumerate(reqs):
-        for j in range(k):
-            if r.corrupt_draw[j] < r.corrupt_p:
-                drafts[b, j] = r.random_tokens[j]
+    nd = [r.n_draft for r in reqs]                                         # candidates per request (ragged for the interleaved workload)
+    ragged = len(set(nd)) > 1
+    parents_dev = None
+    if wl.draft == "tree":
+        # trees: the workload's seeded topologies; node 0 carries the slot's own prediction, the others random ids
+        # (acceptance stops early, the forward pass is the same work)
+        pars = np.stack([synth.tree_parents(wl.seed, b, k, wl.tree_depth) for b in range(B)]).astype(np.int32)
+        parents_dev = torch.tensor(pars, device="cuda")
+        drafts = np.stack([r.random_tokens[:k] for r in reqs]).astype(np.int32)
+        drafts[:, 0] = nt0
+    else:
+        # chains: the model's own greedy continuation (k-1 single-token verify+commit rounds through the
+        # library), then each position replaced by a random id with probability p
+        g = np.zeros((B, k), dtype=np.int32)
+        g[:, 0] = nt0
+        cur = list(lens)
+        for i in range(1, k):
+            a, bt = sev.verify(model, batch.kv, cur, torch.tensor(g[:, i - 1:i].copy(), device="cuda"), None, B, 1)
+            sev.kv_commit(batch.kv, None, B)
+            torch.cuda.synchronize()
+            assert int(a.min()) == 1
+            g[:, i] = bt.cpu().numpy()
+            cur = [c + 1 for c in cur]
+        drafts = g.copy()
+        for b, r in enumerate(reqs):
+            for j in range(k):
+                if r.corrupt_draw[j] < r.corrupt_p:
+                    drafts[b, j] = r.random_tokens[j]
     d_dev = torch.tensor(drafts, device="cuda")
     acc = torch.empty(B, dtype=torch.int32, device="cuda")
     bon = torch.empty(B, dtype=torch.int32, device="cuda")
@@ -101,8 +112,10 @@ def main():
             sev.verify_sample(model, batch.kv, lens, d_dev, k, q_dev, u_acc, u_emit, 0.7, out=s_out)
         elif args.padded_kv:
             sev.verify_ex(model, batch.kv, lens, d_dev, k, mode=2, accept_len=acc, bonus_token=bon)
+        elif ragged:
+            sev.verify_ex(model, batch.kv, lens, d_dev, k, draft_lens=nd, accept_len=acc, bonus_token=bon)
         else:
-            sev.verify(model, batch.kv, lens, d_dev, None, B, k, acc, bon)
+            sev.verify(model, batch.kv, lens, d_dev, parents_dev, B, k, acc, bon)
         sev.kv_commit(batch.kv, None, B)
         batch.kv.set_state(None, lens, nt0)
 
@@ -159,21 +172,22 @@ def main():
     gu_bytes = 2 * shape.d_ffn * shape.d_model * 2                      # gate and up matrices, bf16, read once
     gu_avg_ms = gu_ms / max(gu_n, 1)
     achieved = gu_bytes / (gu_avg_ms * 1e-3) / 1e9
-    step_bytes = shape.streamed_params() * 2 + sum(P + k for P in lens) * shape.kv_bytes_per_token()
-    tokens = B * k
+    step_bytes = shape.streamed_params() * 2 + sum(P + n for P, n in zip(lens, nd)) * shape.kv_bytes_per_token()
+    tokens = sum(nd)
     traffic, traffic_note = traffic_from_profile(wl.name)
-    classes_out = kernel_class_table(shape, tokens, lens, k, per_class, empty_ms)
+    classes_out = kernel_class_table(shape, tokens, lens, nd, per_class, empty_ms)
     out = {
         "metric": ("COMPARISON RUN (accept / resample rule at temperature 0.7): verified draft tokens/sec on 1 MI355X" if args.stochastic else
                    "COMPARISON RUN (padded KV + dense mask): verified draft tokens/sec on 1 MI355X" if args.padded_kv else
-                   "verified draft tokens/sec on 1 MI355X (8B-shape bf16, B=16, k=8); % roofline"),
+                   "verified draft tokens/sec on 1 MI355X (8B-shape bf16, B=16, k=8); % roofline" if wl.name == "8b-chain-b16k8" else
+                   f"OTHER WORKLOAD ({wl.name}), not the headline: verified draft tokens/sec on 1 MI355X"),
         "value": tokens / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "emitted_tokens_per_s": float((accept + 1).sum()) / (ms_per_step * 1e-3),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "model_shape": shape.name, "B": B, "k": k, "rows_per_step": tokens,
+        "config": {"workload": wl.name, "model_shape": shape.name, "B": B, "k": k, "draft": wl.draft, "rows_per_step": tokens,
                    "sum_prefix_tokens": int(sum(lens)), "page_size": 16,
                    "padded_kv": bool(args.padded_kv), "stochastic": bool(args.stochastic), "mean_accept_len": float(accept.mean()),
                    "accept_len": [int(a) for a in accept], "precision": "bf16 weights/KV, split-bf16 activations, f32 accumulate"},
@@ -192,7 +206,7 @@ def main():
                          "32-token tree at batch 1 on an A100 80 GB",
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, shape, reqs, lens, drafts, nt0)
+        out["cpu_baseline"] = cpu_baseline(wl, shape, reqs, lens, drafts, nt0, nd, None if parents_dev is None else pars)
     print(json.dumps(out), flush=True)
 
 
@@ -230,7 +244,7 @@ def traffic_from_profile(workload):
     return val, f"profiles/{os.path.basename(path)}"
 
 
-def kernel_class_table(shape, rows, lens, k, per_class_ms, empty_ms):
+def kernel_class_table(shape, rows, lens, nd, per_class_ms, empty_ms):
     """Per kernel class of one step: algorithmic bytes and FLOP per launch span, event-timed duration, and the fraction
     of both rooflines (HBM 8 TB/s; dense bf16 matrix cores 2.5 PFLOP/s).  'mfma_useful' counts 2*M*N*K once; the
     split-bf16 activations make the matrix cores issue twice that ('mfma_issued').  'binding' is the roofline whose
@@ -238,9 +252,9 @@ def kernel_class_table(shape, rows, lens, k, per_class_ms, empty_ms):
     about empty_event_pair_ms to every span (reported, not subtracted)."""
     d, F, V, L = shape.d_model, shape.d_ffn, shape.vocab, shape.n_layers
     qkv_n = shape.q_dim + 2 * shape.kv_dim
-    kv_tokens = sum(P + k for P in lens)
+    kv_tokens = sum(P + n for P, n in zip(lens, nd))
     att_bytes = kv_tokens * 2 * shape.kv_dim * 2
-    att_flop = 4 * shape.q_dim * sum(k * (P + k) for P in lens)
+    att_flop = 4 * shape.q_dim * sum(n * (P + n) for P, n in zip(lens, nd))
     spec = {
         "gemm_qkv": (qkv_n * d * 2, 2 * rows * qkv_n * d, L),
         "gemm_o": (d * shape.q_dim * 2, 2 * rows * d * shape.q_dim, L),
@@ -264,7 +278,7 @@ def kernel_class_table(shape, rows, lens, k, per_class_ms, empty_ms):
     return out
 
 
-def cpu_baseline(wl, shape, reqs, lens, drafts, nt0):
+def cpu_baseline(wl, shape, reqs, lens, drafts, nt0, nd, pars):
     """The CPU oracle's verify step (all requests, all layers, LM head, acceptance) timed on the host cores as it stands:
     weights widened to float32 once (not timed), then whole passes with the BLAS threads the process has, and one
     pass with a single thread.  Bounded sample: at most about 15 s of passes per leg."""
@@ -293,16 +307,17 @@ def cpu_baseline(wl, shape, reqs, lens, drafts, nt0):
             om.w(nm, l)
         if l % 8 == 7:
             log(f"  oracle weights widened up to layer {l}  ({time.perf_counter() - t0:.0f}s)")
-    blocks = [drafts[b] for b in range(len(lens))]
+    blocks = [drafts[b][:nd[b]] for b in range(len(lens))]
+    par_list = None if pars is None else [pars[b] for b in range(len(lens))]
 
     def timed(budget_s, max_reps):
         reps, t = 0, time.perf_counter()
         while reps < 1 or (time.perf_counter() - t < budget_s and reps < max_reps):
-            vo.verify(om, caches, blocks)
+            vo.verify(om, caches, blocks, par_list)
             reps += 1
         return (time.perf_counter() - t) / reps, reps
 
-    vo.verify(om, caches, blocks)                                            # warm-up (page faults, BLAS thread start)
+    vo.verify(om, caches, blocks, par_list)                                  # warm-up (page faults, BLAS thread start)
     full, reps = timed(12.0, 20)
     try:
         from threadpoolctl import threadpool_info, threadpool_limits
@@ -312,7 +327,7 @@ def cpu_baseline(wl, shape, reqs, lens, drafts, nt0):
     except Exception:
         blas, one, reps1 = os.cpu_count(), None, 0
     log(f"oracle verify, full depth: {full:.3f}s per pass on {blas} BLAS threads ({reps} passes); 1 thread: {one}")
-    n_tok = len(lens) * wl.k_max
+    n_tok = int(sum(nd))
     return {"value": n_tok / full, "unit": "tokens/s", "cores": int(min(blas, len(os.sched_getaffinity(0)))),
             "kind": "oracle", "seconds_per_step": full,
             "single_thread": None if one is None else {"value": n_tok / one, "unit": "tokens/s", "cores": 1, "seconds_per_step": one},

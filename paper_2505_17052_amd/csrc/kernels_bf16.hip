@@ -183,8 +183,8 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(const uint16_t *E, cons
 // grid: 1-D over (column group, split-K slice, row block of MT tiles); see the block index decode.
 //
 // Split-K.  With S = 1 the block runs the epilogue itself.  With S > 1 it stores its accumulators
-// in register order (coalesced 1 KiB stores) and gemm_fixup_kernel, one wave per 32x32 output
-// tile, adds the S slices in slice order and runs the same epilogue code.
+// in register order (coalesced 1 KiB stores, layout [slice][column tile][row tile]) and gemm_fixup_kernel,
+// one wave per 32x32 output tile, adds the S slices in slice order and runs the same epilogue code.
 //
 // Normalisation.  RMSNorm scales row m by r[m] = 1/rms(h[m]) and column k by the gain g[k].  The
 // producer of an activation matrix writes split(h * g) and the rows' sums of squares; the
@@ -206,7 +206,7 @@ struct GemmArgs {
     const uint4 *X;          // xpack activations
     int n_tiles, k_steps, m_tiles_total, M, N;
     int col_groups, m_blocks, splits, mt, nt;   // grid decomposition (see the kernel's block index decode)
-    float *part;             // split-K exchange: [S][col group][row block][wave][NT][MT][4][64] float4
+    float *part;             // split-K exchange: [S][column tile][row tile][4][64 lanes] float4
     const unsigned long long *ssq_in;   // [rows] sums of squares of the input rows, or null (input is not a normed stream)
     float inv_d, eps;
     // EPI_RESID
@@ -617,18 +617,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
 
     // ------------------------------------------------------------------ split-K: hand the slice to the fix-up kernel
     if (g.splits > 1) {
-        const size_t per_block = (size_t)4 * NT * MT * 4 * 64;          // float4 per block
-        const size_t blk = (size_t)cg * g.m_blocks + mb;
-        float4 *mine = (float4 *)g.part + ((size_t)split * g.col_groups * g.m_blocks + blk) * per_block +
-                       (size_t)wave * (NT * MT * 4 * 64) + lane;
+        // exchange layout [slice][column tile][row tile][4][64 lanes] float4: register order, 1 KiB per store instruction
 #pragma unroll
         for (int a = 0; a < NT; ++a)
+            if (a < my_tiles) {
 #pragma unroll
-            for (int b = 0; b < MT; ++b)
+                for (int b = 0; b < MT; ++b) {
+                    float4 *mine = (float4 *)g.part + (((size_t)split * g.n_tiles + tile0 + a) * g.m_tiles_total + mt0 + b) * 256 + lane;
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    mine[((a * MT + b) * 4 + j) * 64] =
-                        make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+                    for (int j = 0; j < 4; ++j)
+                        mine[j * 64] = make_float4(acc[a][b][4 * j], acc[a][b][4 * j + 1], acc[a][b][4 * j + 2], acc[a][b][4 * j + 3]);
+                }
+            }
         return;
     }
 
@@ -693,252 +693,27 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     }
 }
 
-// ---------------------------------------------------------------------------
-// Row-split GEMM with loader waves, for 3 or more row tiles (the verification batches of 128 rows and up).
-//
-// A block computes 128 rows x CT column tiles and has 8 waves with two roles:
-//   * waves 4..7 only load: they stream the block's weight fragments from global memory straight into an
-//     LDS ring of D stages (load-to-LDS instructions: no staging registers, no LDS store instructions), many
-//     stages ahead of their use, and hand a stage over once its loads have landed;
-//   * waves 0..3 only multiply: wave w owns row tile w and all CT column tiles; it reads the weight fragments
-//     of a stage from the ring and its own two activation planes straight from global memory (they are its
-//     own rows: nothing to share), and issues the MFMAs.
-// Why this shape.  (1) Every weight byte enters exactly one compute unit: with 64-row blocks two units
-// request every weight line, and what a unit can absorb is bounded by its weight misses.  (2) The ring holds
-// 128 KiB of weights in flight per unit, far more than registers can stage, and its depth absorbs the
-// jitter of the misses; the activation planes (L2 hits) are prefetched PFX stages ahead in registers.
-// (3) The multiplying waves' instruction stream is LDS reads, a few global loads and MFMAs only.
-// MFMA operand order as in gemm_bf16_kernel (A = weights, B = activations): same accumulator layout, same
-// epilogues.  One barrier per stage keeps the roles in step: at the barrier that ends stage t the loaders
-// guarantee that stage t + 2 has landed, because the multiplying waves read the fragments of stage t + 1
-// during stage t.  Both roles execute exactly one barrier per stage plus one after the prologue.
-// ---------------------------------------------------------------------------
-#define RS_RING_BYTES (128 * 1024)
-
-__device__ __forceinline__ void rs_barrier() { asm volatile("s_barrier" ::: "memory"); }
-
-// waits until at most n of this wave's loads are outstanding (n uniform, 0 <= n <= 48); the immediate of
-// s_waitcnt must be a constant
-__device__ __forceinline__ void rs_wait_loads(int n) {
-#define RS_W(i) case i: asm volatile("s_waitcnt vmcnt(" #i ")" ::: "memory"); break;
-    switch (n) {
-        RS_W(0) RS_W(1) RS_W(2) RS_W(3) RS_W(4) RS_W(5) RS_W(6) RS_W(7) RS_W(8) RS_W(9) RS_W(10) RS_W(11) RS_W(12) RS_W(13) RS_W(14) RS_W(15)
-        RS_W(16) RS_W(17) RS_W(18) RS_W(19) RS_W(20) RS_W(21) RS_W(22) RS_W(23) RS_W(24) RS_W(25) RS_W(26) RS_W(27) RS_W(28) RS_W(29) RS_W(30)
-        RS_W(31) RS_W(32) RS_W(33) RS_W(34) RS_W(35) RS_W(36) RS_W(37) RS_W(38) RS_W(39) RS_W(40) RS_W(41) RS_W(42) RS_W(43) RS_W(44) RS_W(45)
-        RS_W(46) RS_W(47) RS_W(48)
-    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-    }
-#undef RS_W
-}
-
-template <int CT, int EPI>
-__global__ __launch_bounds__(512) void gemm_rs_kernel(const uint4 *W_, const uint4 *X_, int n_tiles_, int k_steps_, int m_tiles_total_,
-                                                      int col_groups_, int m_blocks_, int splits_, GemmArgs g) {
-    g.W = W_; g.X = X_; g.n_tiles = n_tiles_; g.k_steps = k_steps_; g.m_tiles_total = m_tiles_total_;
-    g.col_groups = col_groups_; g.m_blocks = m_blocks_; g.splits = splits_;
-    constexpr int KS = 2;                               // k-steps of 16 per stage
-    constexpr int STAGE_U4 = KS * CT * 64;              // 16-byte units of weights per stage
-    constexpr int D = RS_RING_BYTES / (STAGE_U4 * 16);  // ring depth in stages (a power of two)
-    constexpr int LPS = KS * CT / 4;                    // load instructions per loader wave and stage
-    constexpr int PFX = 4;                              // stages of activation planes in flight per multiplying wave
-    static_assert((D & (D - 1)) == 0 && D >= 4 && (KS * CT) % 4 == 0 && PFX % 2 == 0 && (D - 1) * LPS <= 48, "ring geometry");
-    extern __shared__ u32x4 ring[];                     // [D stages][KS][CT][64 lanes]
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int q = blockIdx.x >> 3;                            // block index decode as in gemm_bf16_kernel
-    const int mb = q % g.m_blocks;
-    q /= g.m_blocks;
-    const int split = q % g.splits;
-    const int cg = (q / g.splits) * 8 + (blockIdx.x & 7);
-    if (cg >= g.col_groups) return;                     // whole block leaves before any barrier
-    const int tile0 = cg * CT;
-    const int n_stages = g.k_steps / KS;
-    const int s_begin = (int)((unsigned)n_stages * (unsigned)split / (unsigned)g.splits);
-    const int s_end = (int)((unsigned)n_stages * (unsigned)(split + 1) / (unsigned)g.splits);
-    const int n = s_end - s_begin;                      // stages of this block (uniform over the block: both roles count the same barriers)
-    // every column group starts its K walk at another stage (see gemm_bf16_kernel)
-    const int rot = n >= 64 ? (int)((unsigned)cg * (unsigned)n / (unsigned)g.col_groups) : 0;
-    auto phys = [&](int t) {                            // logical stage (clamped to the slice) -> stage index in K
-        int i = min(t, n - 1) + rot;
-        if (i >= n) i -= n;
-        return s_begin + i;
-    };
-
-    if (wave >= 4) {
-        // ------------------------------------------------------------------ loader waves
-        const int p = wave - 4;
-        const u32x4 *wsrc[LPS];                         // this lane's 16 bytes of fragment f = p * LPS + i of a stage: k-step f / CT, tile f % CT
-        int dst_off[LPS];
-#pragma unroll
-        for (int i = 0; i < LPS; ++i) {
-            const int f = p * LPS + i, ks = f / CT, tl = f % CT;
-            const int t = min(tile0 + tl, g.n_tiles - 1);           // a block at the matrix edge re-reads a valid tile (never stored)
-            wsrc[i] = (const u32x4 *)g.W + ((size_t)t * g.k_steps + ks) * 64 + lane;
-            dst_off[i] = (ks * CT + tl) * 64;
-        }
-        auto issue = [&](int t) {                       // all loads of logical stage t, into ring slot t % D
-            const size_t so = (size_t)phys(t) * (KS * 64);
-            u32x4 *slot = ring + (t & (D - 1)) * STAGE_U4;
-#pragma unroll
-            for (int i = 0; i < LPS; ++i)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(wsrc[i] + so),
-                                                 (__attribute__((address_space(3))) void *)(slot + dst_off[i]), 16, 0, 2 /* streaming hint */);
-        };
-        const int pre = min(D - 1, n);                  // stages 0 .. pre - 1 go out before the loop
-        for (int t = 0; t < pre; ++t) issue(t);
-        rs_wait_loads(max(pre - 2, 0) * LPS);           // stages 0 and 1 have landed
-        rs_barrier();
-        for (int it = 0; it < n; ++it) {
-            // slot (it + D - 1) % D held stage it - 1, whose fragments the multiplying waves read during stage it - 2
-            if (it + D - 1 < n) issue(it + D - 1);
-            const int last = min(it + D - 1, n - 1);    // newest stage requested so far
-            rs_wait_loads(max(last - (it + 2), 0) * LPS);           // stage it + 2 has landed (everything older too: loads return in order)
-            rs_barrier();
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        return;
-    }
-
-    // ---------------------------------------------------------------------- multiplying waves
-    const int rt = mb * 4 + wave;                       // this wave's row tile (the activation buffer always holds a multiple of 4 row tiles)
-    const int mrow = lane & 31, nsub = 4 * (lane >> 5);
-    const int m = rt * 32 + mrow;
-    f32x16 acc[CT];
-#pragma unroll
-    for (int f = 0; f < CT; ++f)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[f][r] = 0.f;
-    const u32x4 *xp = (const u32x4 *)g.X + (size_t)rt * 128 + lane;      // [k-step][row tile][plane][lane]
-    const size_t x_kstep = (size_t)g.m_tiles_total * 128;
-    u32x4 xreg[PFX][KS][2];                             // activation planes of stages st .. st + PFX - 1
-    u32x4 wf[2][KS][CT];                                // weight fragments of the current and the next stage
-#pragma unroll
-    for (int u = 0; u < PFX; ++u) {
-        const int sx = phys(u);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int pl = 0; pl < 2; ++pl) xreg[u][ks][pl] = xp[(size_t)(KS * sx + ks) * x_kstep + pl * 64];
-    }
-    const unsigned long long sq_row = (g.splits == 1 && g.ssq_in && m < g.M) ? g.ssq_in[m] : 0ull;
-    if constexpr (EPI == EPI_QKV) SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.row_cs), "s"(g.q_planes));
-    else SEV_ARGS_NOW("s"(g.part), "s"(g.ssq_in), "s"(g.act));
-    rs_barrier();                                       // stages 0 and 1 are in the ring
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int f = 0; f < CT; ++f) wf[0][ks][f] = ring[(ks * CT + f) * 64 + lane];
-
-    auto group = [&](int base, auto load_tag) {
-        constexpr bool LOAD = decltype(load_tag)::value;
-#pragma unroll
-        for (int u = 0; u < PFX; ++u) {
-            const int st = base + u;
-            if constexpr (!LOAD) {
-                if (st >= n) break;                     // (uniform) the slice has ended: no further barrier on either side
-            }
-            const int cur = u & 1, nxt = cur ^ 1;
-            const u32x4 *wnext = ring + ((st + 1) & (D - 1)) * STAGE_U4 + lane;      // stage st + 1 (beyond the slice: stale data, never multiplied)
-            const int sx = phys(st + PFX);
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl) {
-                    const bf16x8 x = as_bf16x8(xreg[u][ks][pl]);
-#pragma unroll
-                    for (int f = 0; f < CT; ++f) {
-                        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(wf[cur][ks][f]), x, acc[f], 0, 0, 0);
-                        if (pl == 1) wf[nxt][ks][f] = wnext[(ks * CT + f) * 64];
-                    }
-                    if constexpr (LOAD) xreg[u][ks][pl] = xp[(size_t)(KS * sx + ks) * x_kstep + pl * 64];
-                }
-            // the same order for the instruction scheduler (0x008 MFMA, 0x100 DS read, 0x020 VMEM read)
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                for (int pl = 0; pl < 2; ++pl) {
-                    if (pl == 0) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, CT, 0);
-                    } else {
-#pragma unroll
-                        for (int f = 0; f < CT; ++f) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                        }
-                    }
-                    if constexpr (LOAD) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                }
-            __builtin_amdgcn_sched_barrier(0);
-            rs_barrier();
-        }
-    };
-    // the slice padded to whole groups: every group but the last keeps loading (prefetches beyond the slice re-read its
-    // last stage), the last one stops at the slice's end
-    const int n_pad = (n + PFX - 1) / PFX * PFX;
-    for (int base = 0; base + PFX < n_pad; base += PFX) group(base, std::true_type{});
-    group(n_pad - PFX, std::false_type{});
-
-    // ------------------------------------------------------------------ split-K: hand the slice to the fix-up kernel
-    if (g.splits > 1) {
-        // canonical exchange layout [slice][column tile][row tile][4][64 lanes] float4 (register order)
-        float4 *mine = (float4 *)g.part + (((size_t)split * g.n_tiles + tile0) * g.m_tiles_total + rt) * 256 + lane;
-#pragma unroll
-        for (int f = 0; f < CT; ++f)
-            if (tile0 + f < g.n_tiles) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    mine[((size_t)f * g.m_tiles_total * 4 + j) * 64] = make_float4(acc[f][4 * j], acc[f][4 * j + 1], acc[f][4 * j + 2], acc[f][4 * j + 3]);
-            }
-        return;
-    }
-    // ------------------------------------------------------------------ epilogue (this wave's row tile x CT column tiles)
-    static_assert(EPI != EPI_ARGMAX, "the LM head keeps the column-split kernel");
-    const float rs = g.ssq_in ? rms_scale(sq_row, g.inv_d, g.eps) : 1.0f;
-    float ss = 0.f;
-#pragma unroll
-    for (int f = 0; f < CT; ++f)
-        if (tile0 + f < g.n_tiles) {
-            const TilePre pre = tile_pre<EPI, true>(g, tile0 + f, m, nsub, rs);
-            ss += tile_epilogue<EPI>(g, acc[f], tile0 + f, m, nsub, pre);
-        }
-    if constexpr (EPI == EPI_RESID) {
-        ss += __shfl_xor(ss, 32);
-        if (lane < 32 && m < g.M) {
-            atomicAdd(g.ssq_out + m, ssq_fix(ss));
-            if (cg == 0) g.ssq_clear[m] = 0ull;
-        }
-    }
-}
-
-// Split-K fix-up: block (column group cg, row tile mt, a) of 4 waves; wave w sums the S slices of the
-// 32x32 tile (column tile (cg*4 + w)*NT + a, row tile mt) in slice order and runs its epilogue.
+// Split-K fix-up: block (group of 4 column tiles, row tile mt) of 4 waves; wave w sums the S slices of the
+// 32x32 tile (column tile 4 * group + w, row tile mt) in slice order and runs its epilogue.
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, const void *pa_, const void *pb_, const unsigned long long *ssq_in_,
-                                                         int col_groups_, int m_blocks_, int geo_, int n_tiles_, int M_, int N_, int heads_,
+                                                         int m_tiles_real_, int m_tiles_total_, int splits_, int n_tiles_, int M_, int N_, int heads_,
                                                          GemmArgs g) {
     __shared__ float red[4][128];
     // leading scalars (preloaded at wave launch): everything the first loads need; pa_ / pb_ are the residual stream and
-    // the gains (EPI_RESID) or the rotary table and the rows' cache locations (EPI_QKV); geo_ = MT | NT << 8 | S << 16,
-    // heads_ = query heads | KV heads << 16
-    g.part = const_cast<float *>(part_); g.ssq_in = ssq_in_; g.col_groups = col_groups_; g.m_blocks = m_blocks_;
-    g.mt = geo_ & 255; g.nt = (geo_ >> 8) & 255; g.splits = geo_ >> 16; g.n_tiles = n_tiles_; g.M = M_; g.N = N_;
+    // the gains (EPI_RESID) or the rotary table and the rows' cache locations (EPI_QKV); heads_ = query heads | KV heads << 16
+    g.part = const_cast<float *>(part_); g.ssq_in = ssq_in_; g.m_tiles_total = m_tiles_total_;
+    g.splits = splits_; g.n_tiles = n_tiles_; g.M = M_; g.N = N_;
     g.Hq = heads_ & 0xffff; g.Hkv = heads_ >> 16;
     if constexpr (EPI == EPI_RESID) { g.h = (float *)const_cast<void *>(pa_); g.gain = (const float *)pb_; }
     if constexpr (EPI == EPI_QKV) { g.row_cs = (const float2 *)pa_; g.row_kvloc = (const int32_t *)pb_; }
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int MT = g.mt, NT = g.nt;
-    int q = blockIdx.x;
-    const int a = q % NT; q /= NT;
-    const int mtn = g.m_blocks * MT;
-    const int mt = q % mtn;
-    const int cg = q / mtn;
-    const int mb = mt / MT, b = mt - mb * MT;
-    const int T = (cg * 4 + wave) * NT + a;
+    const int mt = blockIdx.x % m_tiles_real_, grp = blockIdx.x / m_tiles_real_;
+    const int T = grp * 4 + wave;
     const int mrow = lane & 31, nsub = 4 * (lane >> 5);
     const int m = mt * 32 + mrow;
-    const size_t per_block = (size_t)4 * NT * MT * 4 * 64;
-    const size_t slice_stride = (size_t)g.col_groups * g.m_blocks * per_block;
-    const float4 *src = (const float4 *)g.part + ((size_t)cg * g.m_blocks + mb) * per_block +
-                        (size_t)wave * (NT * MT * 4 * 64) + (size_t)((a * MT + b) * 4) * 64 + lane;
+    const size_t slice_stride = (size_t)g.n_tiles * g.m_tiles_total * 256;
+    const float4 *src = (const float4 *)g.part + ((size_t)min(T, g.n_tiles - 1) * g.m_tiles_total + mt) * 256 + lane;
     f32x16 acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
@@ -972,7 +747,7 @@ __global__ __launch_bounds__(256) void gemm_fixup_kernel(const float *part_, con
     if constexpr (EPI == EPI_RESID) {
         ss += __shfl_xor(ss, 32);
         if (lane < 32) red[wave][mrow] = ss;
-        ssq_commit(g, red, 32, mt * 32, cg == 0 && a == 0);
+        ssq_commit(g, red, 32, mt * 32, grp == 0);
     }
 }
 
@@ -1361,9 +1136,17 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
         if (which == G_GU && c.S == 1 && t >= 3 * c.NT + 1 && t <= 4 * c.NT) c.T = t;
     }
     // the exchange buffer holds S slices of (padded columns) x (padded rows)
-    const size_t slice = (size_t)blocks_of(c) * 4 * c.NT * c.MT * 1024;
+    const size_t slice = (size_t)n_tiles * ((m_tiles + 3) / 4 * 4) * 1024;
     while (c.S > 1 && (size_t)c.S * slice > part_elems) --c.S;
     return c;
+}
+
+// one wave per 32x32 output tile; ga.splits slices in the exchange buffer
+template <int EPI>
+static void launch_fixup(const GemmArgs &ga, int m_tiles, hipStream_t st) {
+    hipLaunchKernelGGL((gemm_fixup_kernel<EPI>), dim3((unsigned)((ga.n_tiles + 3) / 4 * m_tiles)), dim3(256), 0, st, (const float *)ga.part,
+                       EPI == EPI_QKV ? (const void *)ga.row_cs : (const void *)ga.h, EPI == EPI_QKV ? (const void *)ga.row_kvloc : (const void *)ga.gain,
+                       ga.ssq_in, m_tiles, ga.m_tiles_total, ga.splits, ga.n_tiles, ga.M, ga.N, ga.Hq | (ga.Hkv << 16), ga);
 }
 
 template <int EPI>
@@ -1390,31 +1173,8 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
 #undef SEV_BY_NT
 #undef SEV_LAUNCH
     if constexpr (EPI != EPI_ARGMAX) {
-        if (c.S > 1)
-            hipLaunchKernelGGL((gemm_fixup_kernel<EPI>), dim3((unsigned)(ga.col_groups * ga.m_blocks * c.MT * c.NT)), dim3(256), 0,
-                               st, (const float *)ga.part, EPI == EPI_QKV ? (const void *)ga.row_cs : (const void *)ga.h,
-                               EPI == EPI_QKV ? (const void *)ga.row_kvloc : (const void *)ga.gain, ga.ssq_in, ga.col_groups, ga.m_blocks,
-                               ga.mt | (ga.nt << 8) | (ga.splits << 16), ga.n_tiles, ga.M, ga.N, ga.Hq | (ga.Hkv << 16), ga);
+        if (c.S > 1) launch_fixup<EPI>(ga, m_tiles, st);
     }
-}
-
-// Launch of the row-split kernel: CT column tiles per block, S split-K slices.
-template <int EPI>
-static void launch_gemm_rs(GemmArgs ga, int m_tiles, int S, hipStream_t st) {
-    constexpr int CT = 4;
-    ga.col_groups = (ga.n_tiles + CT - 1) / CT;
-    ga.m_blocks = (m_tiles + 3) / 4;
-    ga.splits = S;
-    ga.mt = 1;
-    ga.nt = CT;
-    static bool lds_set = false;                         // the ring is larger than the default dynamic LDS limit
-    if (!lds_set) {
-        hipFuncSetAttribute((const void *)(gemm_rs_kernel<CT, EPI>), hipFuncAttributeMaxDynamicSharedMemorySize, RS_RING_BYTES);
-        lds_set = true;
-    }
-    const int g8 = (ga.col_groups + 7) / 8 * 8;
-    hipLaunchKernelGGL((gemm_rs_kernel<CT, EPI>), dim3((unsigned)(g8 * ga.m_blocks * S)), dim3(512), RS_RING_BYTES, st, ga.W, ga.X, ga.n_tiles,
-                       ga.k_steps, ga.m_tiles_total, ga.col_groups, ga.m_blocks, S, ga);
 }
 
 void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, bool att_direct,
@@ -1484,8 +1244,7 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             GemmArgs ga = base;
             ga.W = Wp(lo.wgu); ga.X = (const uint4 *)xa; ga.n_tiles = d.d_ffn / 16; ga.k_steps = d.d_model / 16;
             ga.N = 2 * d.d_ffn; ga.act = act; ga.ssq_in = kv->ssq[0];
-            if ((kv->tune.rs & 1) && m_tiles_real >= 3) launch_gemm_rs<EPI_SWIGLU>(ga, m_tiles_real, 1, st);
-            else launch_gemm<EPI_SWIGLU>(ga, pg, m_tiles_real, st);
+            launch_gemm<EPI_SWIGLU>(ga, pg, m_tiles_real, st);
         }
         {   // down projection; residual add, next norm's operand and scale in its epilogue
             Prof p(kv, st, PROF_GEMM_DOWN);

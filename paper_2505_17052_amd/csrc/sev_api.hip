@@ -208,7 +208,6 @@ static void read_tune(Tune *t) {
             t->has_gemm[i] = sscanf(e, "%d,%d,%d,%d", &t->gemm[i][0], &t->gemm[i][1], &t->gemm[i][2], &t->gemm[i][3]) == 4;
     if (const char *e = getenv("SEV_TUNE_TPB")) t->tpb = atoi(e);
     if (const char *e = getenv("SEV_TUNE_CP")) t->cp = atoi(e);
-    if (const char *e = getenv("SEV_TUNE_RS")) t->rs = atoi(e);
 }
 
 extern "C" int sev_kv_create(const sev_model *m, int max_requests, int max_rows, int64_t n_pages, int page_size,

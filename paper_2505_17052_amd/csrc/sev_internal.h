@@ -91,7 +91,6 @@ struct Tune {
     int gemm[5][4];
     bool has_gemm[5];
     int tpb, cp;
-    int rs;            // SEV_TUNE_RS: bit mask of the GEMMs that run the row-split kernel (1 gate/up, 2 down, 4 O, 8 QKV)
 };
 
 struct sev_kv {
