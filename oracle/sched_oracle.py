@@ -13,14 +13,16 @@ Everything is written as a plain discrete-event simulation over integer microsec
 a time, with exact rational arithmetic where a rounding rule is involved.
 
 Readings of the paper (it gives the scheme and one worked example, no pseudo-code):
-  * "immediate processing of incoming drafts": a free server starts a batch as soon as one block has
-    arrived (min_batch = 1); min_batch / max_wait_us generalise this to "wait for a fuller batch".
+  * drafts are processed as soon as they come in (the scheduling section's description of the server): a free
+    server starts a batch as soon as one block has arrived (min_batch = 1); min_batch / max_wait_us generalise
+    this to waiting for a fuller batch.
   * order of service: first come, first served, no overtaking; a batch is capped by a request count
     and by a row (draft token) count.
   * depth calibration: nearest integer to (t_verify - rtt) / t_draft_fwd, halves up.  Pinned by the
     paper's example (section "Pipeline-aware draft depth adjustment"): 94.2 ms verification, about
     11 ms per draft pass, depth 7 / 5 / 4 at 15 / 40 / 50 ms RTT; rounding down would give 4 at 40 ms.
-  * "real-time performance measurements": a running estimate est += floor((d - est) / 8).
+  * the depth is set from times measured while serving (same section): a running estimate
+    est += floor((d - est) / 8).
 """
 from fractions import Fraction
 import heapq
