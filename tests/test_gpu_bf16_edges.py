@@ -47,6 +47,42 @@ def test_largest_batch_single_token_drafts(setup):
     assert n_exact >= B // 2
 
 
+def test_maximum_batch_times_maximum_draft_length(setup):
+    """Both interface limits at once: 256 requests (SEV_MAX_BATCH) of up to 64 candidates (SEV_MAX_DRAFT), 15 360 GEMM
+    rows in one call, with a ragged tail (every fourth request sends fewer candidates, some only one).  Every
+    request is compared with the oracle.  The first candidates continue the oracle's greedy decoding for a while
+    (a different number per request), the rest are random ids."""
+    sev, harness, model, om = setup
+    B, k = 256, 64
+    lens = [1 + (11 * b) % 70 for b in range(B)]
+    nd = [k if b % 4 else 1 + (5 * b) % k for b in range(B)]
+    announce(f"edges: B={B} x k<={k}, {sum(nd)} rows")
+    reqs, batch, caches = _make(setup, lens, k, sum(nd))
+    from tests.helpers import greedy_in_place
+    gs = greedy_in_place(om, caches, 6)
+    drafts = np.zeros((B, k), dtype=np.int32)
+    for b in range(B):
+        good = b % 7                                      # 0..6 tokens of the true continuation, then random ids
+        row = np.array(reqs[b].random_tokens[:k], dtype=np.int64)
+        row[:good] = gs[b][:good]
+        if row[good] == gs[b][good]:
+            row[good] = (row[good] + 1) % SHAPE.vocab
+        drafts[b, :nd[b]] = row[:nd[b]]
+        batch.kv.set_state(b, lens[b], caches[b].next_tok)
+    out = sev.verify_ex(model, batch.kv, lens, torch.tensor(drafts, device="cuda"), k, draft_lens=nd, want_path=True,
+                        want_argmax=True, want_logits=True)
+    torch.cuda.synchronize()
+    assert batch.kv.get_state(0)[2] == 0
+    res = vo.verify(om, caches, [drafts[b, :nd[b]] for b in range(B)])
+    n_exact, worst, mean = _compare(out, res, B, k)
+    acc = out["accept_len"].cpu().numpy()
+    announce(f"  exact-compared {n_exact}/{B}, logits max {worst:.2e} mean {mean:.2e}, accept lengths 0..{int(acc.max())}")
+    assert n_exact >= B // 3 and int(acc.max()) >= 4
+    sev.kv_commit(batch.kv, None, B)
+    for b in (0, 1, 37, 128, 255):
+        assert batch.kv.get_state(b) == (lens[b] + int(acc[b]), int(out["bonus_token"][b]), 0)
+
+
 def test_longest_chain_and_page_boundaries(setup):
     sev, harness, model, om = setup
     lens = [16, 17, 15, 32, 1]                            # on, after and before a page boundary; two full pages; one token
