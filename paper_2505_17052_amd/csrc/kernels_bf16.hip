@@ -1158,6 +1158,9 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
         c.NT = 2;
         pick_s();
         if (c.S > 5 || (c.S > 1 && (k_steps / 2) / c.S < 24)) c = narrow;
+        // a GEMM that runs unsplit with 64-row blocks would gain a fix-up kernel: worth it only where those blocks
+        // leave more than 30 % of the compute units idle (QKV at the 70B shape: 160 blocks; not at the 8B shape: 192)
+        else if (narrow.S == 1 && c.S > 1 && blocks_of(narrow) * 10 >= 256 * 7) c = narrow;
     }
     // short slices are mostly pipeline fill: halve the block width instead of splitting that deep
     if (splittable && c.NT == 2 && c.S > 1 && (k_steps / 2) / c.S < 24) {
