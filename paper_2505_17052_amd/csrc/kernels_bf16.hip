@@ -804,7 +804,7 @@ template <int WAVES, bool DIRECT, bool ONCE>
 __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kernel(const int4 *it_a_, const int4 *it_b_, const int32_t *it_pages_,
                                                                                     const uint16_t *q_planes, char *pool_, size_t layer_off_, size_t v_off_,
                                                                                     int M, int heads_,
-                                                                                    DevPlan p, KvGeom g, int n_items,
+                                                                                    DevPlan p, KvGeom g, int n_items_sib,
                                                                                     float *att_o, float2 *att_ml, float scale_log2e,
                                                                                     uint16_t *o_pack, int m_tiles) {
     // (leading scalars: preloaded at wave launch; layer_off_ = layer * layer stride of the pool, v_off_ = offset of the
@@ -814,11 +814,16 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
     g.Hkv = heads_ >> 16;
     g.v_offset = v_off_;
     extern __shared__ float lds[];                    // WAVES merge slots: 64 accumulator registers + max + sum per lane
-    // Block index -> (work item, KV head): the KV head changes fastest among the blocks of one XCD (ids 8 apart), so
-    // that at any moment the running blocks cover every head.  A head's K and V blocks all lie at the same offset
-    // inside the 32 KiB page records: blocks of a single head running together would keep reading the same residues
-    // of the address space.  The grid is padded to whole groups of 8 items; the padding leaves before the barrier.
-    const int item = (int)(blockIdx.x >> 3) / g.Hkv * 8 + (int)(blockIdx.x & 7), kvh = (int)(blockIdx.x >> 3) % g.Hkv;
+    // Block index -> (work item, KV head).  Consecutive block ids go round-robin to the 8 XCDs, each with its own L2;
+    // the blocks of one XCD (ids 8 apart) walk, in this order: the KV heads, the `sib` row groups of one (request, chunk)
+    // - items that read the same K/V, side by side in the work list - and then the next set of row groups.  The blocks
+    // that share a chunk so run on one XCD at about the same time and the chunk comes from memory once (trees of 64
+    // nodes, 8 row groups: 45 ns per page against 78 ns when the groups are spread over the XCDs).  sib = 1 when the
+    // requests differ in their number of row groups.  The grid is padded to whole groups of 8 sets; the padding leaves
+    // before the barrier.
+    const int n_items = n_items_sib & 0xffffff, sib = n_items_sib >> 24;
+    const int jb = (int)(blockIdx.x >> 3), kvh = jb % g.Hkv, tb = jb / g.Hkv;
+    const int item = ((tb / sib) * 8 + (int)(blockIdx.x & 7)) * sib + tb % sib;
     if (item >= n_items) return;
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar: loop bounds stay uniform
     // everything the block needs to know comes from two 16-byte loads and one page-id load, all independent
@@ -1063,7 +1068,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const int4 *mg_rec, con
     // (all arguments are scalars: preloaded at wave launch; one 16-byte record describes the group)
     const int grpi = blockIdx.x, kvh = blockIdx.y;
     const int4 rec = mg_rec[grpi];
-    const int rg = rec.x & 0xffff, cnt = rec.x >> 16, item0 = rec.y, n = rec.z, row0 = rec.w, G = Hq / Hkv;
+    const int rg = rec.x & 0xffff, cnt = rec.x >> 16, item0 = rec.y, n = rec.z & 0xffff, stride = rec.z >> 16, row0 = rec.w, G = Hq / Hkv;
     const int q = threadIdx.x >> 3, d0 = (threadIdx.x & 7) * 16;
     const int R = rg * 32 + q;
     if (R >= G * n) return;
@@ -1078,7 +1083,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const int4 *mg_rec, con
         float4 o[4][4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const size_t base = ((size_t)(item0 + min(c0 + u, cnt - 1)) * Hkv + kvh) * 32 + q;
+            const size_t base = ((size_t)(item0 + min(c0 + u, cnt - 1) * stride) * Hkv + kvh) * 32 + q;
             ml[u] = att_ml[base];
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[u][e] = *(const float4 *)(att_o + base * 128 + d0 + 4 * e);
@@ -1236,7 +1241,7 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
     }
 }
 
-void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, bool att_direct,
+void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, int sib, bool att_direct,
                   float *logits_out, hipStream_t st) {
     const sev_model_desc &d = m->d;
     KvGeom g = sev_kv_geom(kv);
@@ -1280,9 +1285,9 @@ void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, 
             Prof p(kv, st, PROF_ATTN);
             const bool once = n_groups == B;             // one row group per request: every K/V byte is read by one block
 #define SEV_ATTN(WAVES_, DIRECT_, ONCE_, THREADS_, LDS_)                                                                                   \
-    hipLaunchKernelGGL((attn_bf16_kernel<WAVES_, DIRECT_, ONCE_>), dim3((unsigned)((n_items + 7) / 8 * 8 * d.n_kv_heads)), dim3(THREADS_), LDS_, st, \
+    hipLaunchKernelGGL((attn_bf16_kernel<WAVES_, DIRECT_, ONCE_>), dim3((unsigned)((n_items / sib + 7) / 8 * 8 * sib * d.n_kv_heads)), dim3(THREADS_), LDS_, st, \
                        kv->plan.it_a, kv->plan.it_b, kv->plan.it_pages, qp, g.pool, (size_t)l * g.layer_stride, g.v_offset, rows,           \
-                       d.n_q_heads | (d.n_kv_heads << 16), kv->plan, g, n_items, kv->att_o, kv->att_ml, scale_log2e, op, m_tiles)
+                       d.n_q_heads | (d.n_kv_heads << 16), kv->plan, g, n_items | (sib << 24), kv->att_o, kv->att_ml, scale_log2e, op, m_tiles)
             if (att_direct) {                            // one block of 8 waves per (request, row group, KV head): no chunks, no merge
                 const size_t lds = (size_t)(8 * 64 * 64 + 2 * 8 * 64) * 4;      // 8 merge slots
                 if (once) SEV_ATTN(8, true, true, 512, lds); else SEV_ATTN(8, true, false, 512, lds);

@@ -109,11 +109,13 @@ __global__ __launch_bounds__(256) void plan_kernel(PlanArgs a, PlanDev d) {
         // attention work items of this request: its pages are split evenly over my_chunks chunks
         const int pages = (max(P + n, a.pad_tokens) + SEV_PAGE - 1) / SEV_PAGE;
         const int cpp = (pages + my_chunks - 1) / my_chunks;
-        int it = s_item0[t], g0 = s_grp0[t];
+        // item order: chunk by chunk, the row groups of one chunk side by side (the attention kernel puts them on
+        // one XCD, where the chunk is then fetched from memory once for all of them)
+        const int it0 = s_item0[t], g0 = s_grp0[t];
         for (int rg = 0; rg < my_groups; ++rg) {
-            d.p.mg_rec[g0 + rg] = make_int4(rg | (my_chunks << 16), it, n, row0);
-            for (int c = 0; c < my_chunks; ++c, ++it) {
-                const int p0 = c * cpp;
+            d.p.mg_rec[g0 + rg] = make_int4(rg | (my_chunks << 16), it0 + rg, n | (my_groups << 16), row0);
+            for (int c = 0; c < my_chunks; ++c) {
+                const int p0 = c * cpp, it = it0 + c * my_groups + rg;
                 d.p.it_a[it] = make_int4(rg, p0, min(cpp, pages - p0), P);
                 d.p.it_b[it] = make_int4(n, row0, t, slot);
             }

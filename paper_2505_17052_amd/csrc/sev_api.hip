@@ -506,7 +506,7 @@ extern "C" const char *sev_profile_name(int which) {
 // all run at once, one per compute unit, with chunks as small as that allows (measured on the
 // 8B-shape workloads).  Work lists that do not fit even with the largest chunks fall back to 64-page
 // chunks.  The pages of a request are then split evenly over its chunks.
-static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, int *n_groups, bool *direct) {
+static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, int *n_groups, int *sib, bool *direct) {
     const sev_model_desc &d = kv->model->d;
     const int G = d.n_q_heads / d.n_kv_heads;
     static int n_cu = 0;
@@ -518,6 +518,12 @@ static int pick_chunk_pages(const sev_kv *kv, const PlanArgs &pa, int *n_items, 
     }
     int64_t total_groups = 0;
     for (int b = 0; b < pa.B; ++b) total_groups += (G * pa.nd[b] + 31) / 32;
+    // row groups per request when all requests have the same number (the attention kernel then keeps the groups that
+    // share a KV chunk on one XCD), else 1
+    *sib = (G * pa.nd[0] + 31) / 32;
+    for (int b = 1; b < pa.B; ++b)
+        if ((G * pa.nd[b] + 31) / 32 != *sib) *sib = 1;
+    if (*sib > 127) *sib = 1;
     auto items_for = [&](int64_t cp) {
         int64_t items = 0;
         for (int b = 0; b < pa.B; ++b) {
@@ -610,10 +616,10 @@ static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStre
                 return sev_fail(SEV_ENOSPACE, "request %d: padding to %d tokens exceeds the %d pages of slot %d", b, pa.pad_tokens,
                                 kv->host_pages[pa.slot[b]], pa.slot[b]);
     }
-    int n_items = 0, n_groups = 0, cp = 64;
+    int n_items = 0, n_groups = 0, sib = 1, cp = 64;
     bool att_direct = false;
     if (m->d.dtype == SEV_BF16) {
-        cp = pick_chunk_pages(kv, pa, &n_items, &n_groups, &att_direct);
+        cp = pick_chunk_pages(kv, pa, &n_items, &n_groups, &sib, &att_direct);
         if (cp < 0) return sev_fail(SEV_ENOSPACE, "attention work list does not fit");
     }
     kv->plan.causal = c.parents ? 0 : 1;
@@ -622,7 +628,7 @@ static int run_block(const sev_model *m, sev_kv *kv, const BlockCall &c, hipStre
         launch_plan(kv, pa, c.tokens, c.parents, (int)rows, cp, n_items, st);
     }
     if (m->d.dtype == SEV_F32) f32_forward(m, kv, (int)rows, c.B, c.logits, st);
-    else bf16_forward(m, kv, (int)rows, c.B, n_items, n_groups, att_direct, c.logits, st);
+    else bf16_forward(m, kv, (int)rows, c.B, n_items, n_groups, sib, att_direct, c.logits, st);
     {
         Prof p(kv, st, PROF_OTHER);
         if (c.draft_probs)

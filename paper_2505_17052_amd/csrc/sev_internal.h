@@ -73,7 +73,7 @@ struct DevPlan {
     // b = {draft nodes, first row, request, 0}; pages = physical page ids of the chunk, SEV_ATT_MAX_CP per item
     int4 *it_a, *it_b;
     int32_t *it_pages;
-    int4 *mg_rec;             // [merge groups] {row group | chunks << 16, first work item, draft nodes, first row}
+    int4 *mg_rec;             // [merge groups] {row group | chunks << 16, first work item, draft nodes | item stride << 16, first row}
     int causal;               // 1: blocks are chains (node i sees nodes <= i; any length), 0: trees (ancestor masks, <= 64 nodes)
 };
 
@@ -175,5 +175,5 @@ void f32_forward(const sev_model *m, sev_kv *kv, int rows, int B, float *logits_
 
 // bf16 path
 void launch_pack_bf16(uint16_t *dst, const uint16_t *src, int n_rows, int K, int mode, int tile_add, hipStream_t st);
-void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, bool att_direct,
+void bf16_forward(const sev_model *m, sev_kv *kv, int rows, int B, int n_items, int n_groups, int sib, bool att_direct,
                   float *logits_out, hipStream_t st);
