@@ -930,10 +930,12 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
         // (no memory access sits under control flow inside a pair step: the compiler's wait counts then stay exact)
         float sc[16];
         float mx = -INFINITY;
+        // sc holds the raw scores (masked ones: -inf); the softmax scale goes into the one multiply-add in front of
+        // each exponential
         if constexpr (!MASKED) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                sc[r] = sh[r] * scale_log2e;
+                sc[r] = sh[r];
                 mx = fmaxf(mx, sc[r]);
             }
         }
@@ -952,12 +954,12 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
             if (j4 >= 2) vis4 = has1 ? vis4 : 0u;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float v = ((vis4 >> r) & 1u) ? sh[4 * j4 + r] * scale_log2e : -INFINITY;
+                const float v = ((vis4 >> r) & 1u) ? sh[4 * j4 + r] : -INFINITY;
                 sc[4 * j4 + r] = v;
                 mx = fmaxf(mx, v);
             }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2e;      // (the scale is positive)
         const float mnew = fmaxf(mrun, mx);
         const float muse = (mnew == -INFINITY) ? 0.f : mnew;
         const float alpha = __builtin_amdgcn_exp2f(mrun - muse);
@@ -966,7 +968,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void attn_bf16_kern
         uint32_t ph[8], pl_[8];
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-            const float p0 = __builtin_amdgcn_exp2f(sc[r] - muse), p1 = __builtin_amdgcn_exp2f(sc[r + 1] - muse);
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r], scale_log2e, -muse));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[r + 1], scale_log2e, -muse));
             ps += p0 + p1;
             split_pack2(p0, p1, ph[r / 2], pl_[r / 2]);
         }
