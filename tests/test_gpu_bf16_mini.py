@@ -250,6 +250,32 @@ def test_trees_more_than_128_rows(setup):
                 assert_bf16_close(vv, caches[b].V[l][lens[b]:L], f"V slot {b} layer {l}")
 
 
+def test_trees_of_different_sizes_in_one_block(setup):
+    """Trees of 64, 40 and 17 nodes in one call: the requests have 8, 5 and 3 groups of 32 query rows per KV head, so the
+    attention work list mixes group counts (the order that keeps a chunk's groups on one XCD needs equal counts and is
+    not taken) and the longest prefix spans several chunks."""
+    sev, harness, model, om = setup
+    lens, nd = [90, 700, 48], [64, 40, 17]
+    announce(f"mini trees of {nd} nodes")
+    reqs, batch, caches = _make(setup, lens, 64, 256)
+    pars = [synth.tree_parents(SEED, b, nd[b], min(8, nd[b])) for b in range(3)]
+    toks = tree_tokens(om, caches, pars, reqs, SHAPE.vocab)
+    for b in range(3):
+        batch.kv.set_state(b, lens[b], caches[b].next_tok)
+    tok_arr = np.full((3, 64), -7, dtype=np.int32)           # padding beyond the draft lengths must be ignored
+    par_arr = np.full((3, 64), -5, dtype=np.int32)
+    for b in range(3):
+        tok_arr[b, :nd[b]] = toks[b]
+        par_arr[b, :nd[b]] = pars[b]
+    out = sev.verify_ex(model, batch.kv, lens, torch.tensor(tok_arr, device="cuda"), 64, draft_lens=nd,
+                        parents=torch.tensor(par_arr, device="cuda"), want_path=True, want_argmax=True, want_logits=True)
+    torch.cuda.synchronize()
+    assert batch.kv.get_state(0)[2] == 0
+    res = vo.verify(om, caches, toks, pars)
+    n_exact, worst, mean = _compare(out, res, 3, 64)
+    announce(f"  accept {[r.accept_len for r in res]}, exact-compared {n_exact}/3, logits max {worst:.2e} mean {mean:.2e}")
+
+
 def test_long_prefix_many_chunks(setup):
     sev, harness, model, om = setup
     lens = [2500, 1030]
