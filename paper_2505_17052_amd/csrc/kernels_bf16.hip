@@ -373,7 +373,8 @@ __device__ __forceinline__ float tile_epilogue(const GemmArgs &g, const f32x16 &
 
 // Adds a block's per-row sums of squares (one value per lane < 32 and wave, in red[wave][row]) to
 // ssq_out and clears ssq_clear; rows = number of rows covered, m0 = first row.
-__device__ __forceinline__ void ssq_commit(const GemmArgs &g, float (*red)[128], int rows, int m0, bool clear) {
+template <int STRIDE>
+__device__ __forceinline__ void ssq_commit(const GemmArgs &g, float (*red)[STRIDE], int rows, int m0, bool clear) {
     __syncthreads();
     if ((int)threadIdx.x < rows) {
         const int t = threadIdx.x, m = m0 + t;
@@ -405,7 +406,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const uint4 *W_, const u
     constexpr int XI = KS * MT / 2;                     // 16-byte activation loads per thread and stage
     static_assert(KS * MT % 2 == 0, "a stage of activations must be a whole number of 4 KiB");
     extern __shared__ u32x4 xs[];                       // [2 buffers][KS k-steps][MT][2 planes][64 lanes]
-    __shared__ float red[4][128];
+    __shared__ float red[4][MT * 32 < 128 ? 128 : MT * 32];
     constexpr int STAGE_U4 = KS * MT * 2 * 64;          // uint4 per stage
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // Block index decode, XCD-aware: consecutive block ids go round-robin to the 8 XCDs, each with its
@@ -1137,7 +1138,7 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
     c.MT = (which == G_LM && m_tiles >= 3) ? 4 : (m_tiles >= 2 ? 2 : 1);
     c.NT = (n_tiles % 2 == 0) ? 2 : 1;
     if (which == G_LM && c.MT == 4) c.NT = 4;            // never split: the widest tile halves the activation re-reads
-    if (which == G_GU && m_tiles >= 4 && ((m_tiles + 3) / 4) * ((n_tiles + 15) / 16) >= 200) {
+    if (which == G_GU && m_tiles == 4 && ((n_tiles + 15) / 16) >= 200) {
         c.MT = 4;                                        // enough rows to fill the chip with 128 x 512 blocks, no split needed
         c.NT = 4;
     }
@@ -1155,20 +1156,36 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
         c.S = std::min(c.S, std::max(1, (k_steps / 2) / 8));          // at least 8 stages per slice
     };
     pick_s();
-    // From 256 rows on the matrix pipe binds the projections, and a block of 128 rows issues twice the MFMAs per stage,
-    // barrier and weight fragment of a 64-row block.  Taken when the row tiles fill such blocks (at most a tenth of the
-    // issued tiles empty) and the split that then fills the chip stays shallow with long slices; measured on the 8B and
-    // 70B shapes at 256 and 512 rows: QKV -23 %, down -7 %, O -4 % at the 70B shape, down -5 % at the 8B shape, the
-    // rest unchanged.
-    if (splittable && which != G_GU && m_tiles >= 8 && (m_tiles + 3) / 4 * 40 <= m_tiles * 11 && n_tiles % 2 == 0) {
+    // From 5 row tiles on (more than 128 rows) the matrix pipe starts to bind and the shape of the row blocks decides
+    // how many rounds of blocks the chip needs: rows in as few blocks as 5 row tiles per block allow (5 -> 5, 6 -> 3 + 3,
+    // 7 -> 4 + 4, 9 -> 5 + 5, ... 16 -> 4 x 4), because every row block re-reads the weights through the L2s and issues
+    // its own barriers.  Measured on the 8B and 70B shapes at 160 ... 512 rows (per GEMM, fix-up included): gate/up
+    // -17 ... -25 % at 160, 192, 288 and 320 rows, down -5 ... -32 %, QKV -17 ... -25 % where it applies.
+    const int m_total = (m_tiles + 3) / 4 * 4;           // row tiles of the operand buffers (blocks must stay inside)
+    int few = (m_tiles + 4) / 5, mt_few = (m_tiles + few - 1) / few;
+    if (few * mt_few > m_total) { few = (m_tiles + 3) / 4; mt_few = 4; }      // (4 always fits the padding)
+    if (which != G_LM && m_tiles >= 5 && n_tiles % 2 == 0) {
         const GemmCfg narrow = c;
-        c.MT = 4;
+        c.MT = mt_few;
         c.NT = 2;
         pick_s();
-        if (c.S > 5 || (c.S > 1 && (k_steps / 2) / c.S < 24)) c = narrow;
-        // a GEMM that runs unsplit with 64-row blocks would gain a fix-up kernel: worth it only where those blocks
-        // leave more than 30 % of the compute units idle (QKV at the 70B shape: 160 blocks; not at the 8B shape: 192)
-        else if (narrow.S == 1 && c.S > 1 && blocks_of(narrow) * 10 >= 256 * 7) c = narrow;
+        if (which == G_GU) {
+            // never split: compare with the 128 x 512 blocks by rounds of blocks x tiles per block (the wide block's
+            // tiles are 14 % cheaper: one weight fragment feeds four row tiles and the stage has one barrier)
+            GemmCfg wide = c;
+            wide.MT = 4; wide.NT = 4;
+            const double cost_few = (double)((blocks_of(c) + 255) / 256) * c.MT * c.NT;
+            const double cost_wide = (double)((blocks_of(wide) + 255) / 256) * 16 * 0.86;
+            if (cost_wide < cost_few) c = wide;
+        } else {
+            // split GEMMs: the slices must stay long (64 k-steps); and a GEMM that runs unsplit in one round of 64-row
+            // blocks keeps them, rather than gain a fix-up kernel, when they occupy more units than the split blocks
+            // would (as many, if K is short: the fix-up then costs more than the larger tiles save)
+            const int wide_blocks = blocks_of(c) * c.S, narrow_blocks = blocks_of(narrow);
+            if (c.S > 1 && k_steps / c.S < 64) c = narrow;
+            else if (narrow.S == 1 && c.S > 1 && narrow_blocks <= 256 &&
+                     (narrow_blocks > wide_blocks || (narrow_blocks == wide_blocks && k_steps < 512))) c = narrow;
+        }
     }
     // short slices are mostly pipeline fill: halve the block width instead of splitting that deep
     if (splittable && c.NT == 2 && c.S > 1 && (k_steps / 2) / c.S < 24) {
@@ -1177,9 +1194,10 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
     }
     if (tune.has_gemm[which]) {                          // "MT,NT,S,PF"; S = 0 keeps the automatic split
         const int mt = tune.gemm[which][0], nt = tune.gemm[which][1], sp = tune.gemm[which][2], pf = tune.gemm[which][3];
-        if ((mt == 1 || mt == 2 || mt == 4) && (nt == 1 || nt == 2 || (nt == 4 && mt == 4 && pf == 4)) &&
-            sp >= 0 && sp <= 32 && (pf == 4 || (pf == 6 && mt <= 2))) {
-            c.MT = std::min(mt, m_tiles >= 3 ? 4 : (m_tiles == 2 ? 2 : 1));
+        if (mt >= 1 && mt <= 5 && (nt == 1 || nt == 2 || (nt == 4 && mt == 4 && pf == 4)) &&
+            sp >= 0 && sp <= 32 && (pf == 4 || (pf == 6 && mt <= 2)) &&
+            (m_tiles + mt - 1) / mt * mt <= (m_tiles + 3) / 4 * 4) {     // the row blocks must stay inside the padded row tiles
+            c.MT = mt;
             c.NT = (nt == 4 && c.MT != 4) ? 2 : nt;
             c.PF = pf;
             pick_s();
@@ -1234,7 +1252,9 @@ static void launch_gemm(GemmArgs ga, const GemmCfg &c, int m_tiles, hipStream_t 
         if (c.NT == 2) SEV_LAUNCH(MT_, 2, PF_); else SEV_LAUNCH(MT_, 1, PF_);                                         \
     } while (0)
     if (c.MT == 4 && c.NT == 4) SEV_LAUNCH(4, 4, 4);
+    else if (c.MT == 5) SEV_BY_NT(5, 4);
     else if (c.MT == 4) SEV_BY_NT(4, 4);
+    else if (c.MT == 3) SEV_BY_NT(3, 4);
     else if (c.MT == 2) { if (c.PF == 6) SEV_BY_NT(2, 6); else SEV_BY_NT(2, 4); }
     else { if (c.PF == 6) SEV_BY_NT(1, 6); else SEV_BY_NT(1, 4); }
 #undef SEV_BY_NT
