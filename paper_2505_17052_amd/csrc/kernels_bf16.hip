@@ -1178,13 +1178,35 @@ static GemmCfg choose_cfg(int which, int m_tiles, int n_tiles, int k_steps, size
             const double cost_wide = (double)((blocks_of(wide) + 255) / 256) * 16 * 0.86;
             if (cost_wide < cost_few) c = wide;
         } else {
-            // split GEMMs: the slices must stay long (64 k-steps); and a GEMM that runs unsplit in one round of 64-row
-            // blocks keeps them, rather than gain a fix-up kernel, when they occupy more units than the split blocks
-            // would (as many, if K is short: the fix-up then costs more than the larger tiles save)
+            // split GEMMs: the slices must stay long (64 k-steps).  O and down (light epilogues) may also take the
+            // 128 x 512 block with more slices; the two are compared by rounds x tiles x (k-steps + pipeline fill) plus
+            // the fix-up's launch and exchange traffic, in units of one tile x k-step (0.055 us)
+            auto cost = [&](const GemmCfg &x) {
+                const double e = x.NT == 4 ? 0.86 : 1.0;
+                double u = (double)((blocks_of(x) * x.S + 255) / 256) * x.MT * x.NT * e * ((double)k_steps / x.S + 24.0);
+                if (x.S > 1) u += (5.0 + (double)x.S * m_tiles * n_tiles * 8192.0 / 6.5e6) / 0.0547;
+                return u;
+            };
+            const GemmCfg few_cfg = c;
+            const bool few_ok = c.S == 1 || k_steps / c.S >= 64;
+            bool wide_ok = false;
+            GemmCfg wide = c;
+            if (which == G_O || which == G_DOWN) {
+                c.MT = 4; c.NT = 4;
+                pick_s();
+                wide = c;
+                wide_ok = (wide.S == 1 || k_steps / wide.S >= 64) && (size_t)wide.S * n_tiles * m_total * 1024 <= part_elems;
+            }
+            if (few_ok && wide_ok) c = cost(wide) < cost(few_cfg) ? wide : few_cfg;
+            else if (few_ok) c = few_cfg;
+            else if (wide_ok) c = wide;
+            else c = narrow;
+            // a GEMM that runs unsplit in one round of 64-row blocks keeps them, rather than gain a fix-up kernel, when
+            // they occupy more units than the split blocks would (as many, if K is short: the fix-up then costs more
+            // than the larger tiles save)
             const int wide_blocks = blocks_of(c) * c.S, narrow_blocks = blocks_of(narrow);
-            if (c.S > 1 && k_steps / c.S < 64) c = narrow;
-            else if (narrow.S == 1 && c.S > 1 && narrow_blocks <= 256 &&
-                     (narrow_blocks > wide_blocks || (narrow_blocks == wide_blocks && k_steps < 512))) c = narrow;
+            if (narrow.S == 1 && c.S > 1 && narrow_blocks <= 256 &&
+                (narrow_blocks > wide_blocks || (narrow_blocks == wide_blocks && k_steps < 512))) c = narrow;
         }
     }
     // short slices are mostly pipeline fill: halve the block width instead of splitting that deep

@@ -276,6 +276,33 @@ def test_trees_of_different_sizes_in_one_block(setup):
     announce(f"  accept {[r.accept_len for r in res]}, exact-compared {n_exact}/3, logits max {worst:.2e} mean {mean:.2e}")
 
 
+@pytest.mark.parametrize("shape_cfg", ["3,2,0,4", "5,2,0,4", "5,1,2,4", "4,4,2,4", "4,2,3,4"])
+def test_forced_gemm_tile_shapes(setup, monkeypatch, shape_cfg):
+    """The GEMM kernel's tile shapes (row tiles per block, column tiles per wave, K slices, prefetch depth) are chosen
+    from the row count and the model's dimensions; the small model reaches only a few of them.  Here each shape is forced
+    for all four projections through the tuning variables (read when the cache handle is created) on a block of 160 rows,
+    and the result is compared with the oracle like any other verify."""
+    sev, harness, model, om = setup
+    for name in ("SEV_TUNE_QKV", "SEV_TUNE_O", "SEV_TUNE_GU", "SEV_TUNE_DOWN"):
+        monkeypatch.setenv(name, shape_cfg)
+    lens = [37 + 11 * b for b in range(20)]
+    announce(f"mini chains 20 x 8 with GEMM tile shape {shape_cfg}")
+    reqs, batch, caches = _make(setup, lens, 8, 160)
+    gs = vo.greedy_continuation(om, caches, 8)
+    drafts = np.stack([gs[b][:8] for b in range(20)]).astype(np.int32)
+    for b in range(0, 20, 3):
+        drafts[b, 1 + b % 6] = (drafts[b, 1 + b % 6] + 1) % SHAPE.vocab
+    for b in range(20):
+        batch.kv.set_state(b, lens[b], caches[b].next_tok)
+    out = sev.verify_ex(model, batch.kv, lens, torch.tensor(drafts, device="cuda"), 8, want_path=True, want_argmax=True,
+                        want_logits=True)
+    torch.cuda.synchronize()
+    assert batch.kv.get_state(0)[2] == 0
+    res = vo.verify(om, caches, [drafts[b] for b in range(20)])
+    n_exact, worst, mean = _compare(out, res, 20, 8)
+    announce(f"  exact-compared {n_exact}/20, logits max {worst:.2e} mean {mean:.2e}")
+
+
 def test_long_prefix_many_chunks(setup):
     sev, harness, model, om = setup
     lens = [2500, 1030]
